@@ -1,0 +1,178 @@
+"""numpy front end of the CPU oracle (``bload_oracle.c``) -- TEST INFRASTRUCTURE.
+
+Only ``tests/``, the smoke check and the benchmark's CPU-baseline leg may use
+this package; the HIP library and its binding never do.  The C file is
+compiled with gcc on first use if the shared object is missing or older than
+the source.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "bload_oracle.c")
+_LIB = os.path.join(_HERE, "libbload_oracle.so")
+
+DTYPE_CODE = {"u8": 0, "f16": 1, "f32": 2, "i32": 3}
+OP_CODE = {"sum": 0, "mean": 1}
+_NP_OF = {"u8": np.uint8, "f16": np.float16, "f32": np.float32, "i32": np.int32}
+
+
+def build(force: bool = False) -> str:
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        subprocess.check_call(["gcc", "-O2", "-Wall", "-Wextra", "-shared", "-fPIC",
+                               "-o", _LIB, _SRC])
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        lib.bload_oracle_splitmix64.restype = ctypes.c_uint64
+        lib.bload_oracle_splitmix64.argtypes = [ctypes.c_uint64, ctypes.c_uint64]
+        lib.bload_oracle_fmix32.restype = ctypes.c_uint32
+        lib.bload_oracle_fmix32.argtypes = [ctypes.c_uint32]
+        lib.bload_oracle_half_to_double.restype = ctypes.c_double
+        lib.bload_oracle_half_to_double.argtypes = [ctypes.c_uint16]
+        lib.bload_oracle_order.restype = None
+        lib.bload_oracle_order.argtypes = [ctypes.c_int64, ctypes.c_uint64, ctypes.c_void_p]
+        lib.bload_oracle_plan.restype = ctypes.c_int
+        lib.bload_oracle_plan.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
+                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        lib.bload_oracle_pack_blocks.restype = None
+        lib.bload_oracle_pack_blocks.argtypes = [ctypes.c_void_p] * 5 + [
+            ctypes.c_int64, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64
+        ] + [ctypes.c_void_p] * 5
+        lib.bload_oracle_segment_reduce.restype = ctypes.c_int
+        lib.bload_oracle_segment_reduce.argtypes = [ctypes.c_void_p, ctypes.c_void_p,
+                                                    ctypes.c_void_p, ctypes.c_int64,
+                                                    ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                                    ctypes.c_void_p]
+        lib.bload_oracle_padding.restype = None
+        lib.bload_oracle_padding.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                                             ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
+                                             ctypes.c_void_p]
+        _lib = lib
+    return _lib
+
+
+def _p(a: np.ndarray):
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def _c(a, dtype) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def splitmix64(seed: int, k: int) -> int:
+    return int(_load().bload_oracle_splitmix64(seed & (2**64 - 1), k))
+
+
+def fmix32(h: int) -> int:
+    return int(_load().bload_oracle_fmix32(h & 0xFFFFFFFF))
+
+
+def half_to_double(bits: int) -> float:
+    return float(_load().bload_oracle_half_to_double(bits))
+
+
+def order(n: int, seed: int) -> np.ndarray:
+    out = np.full(max(n, 0), -7, dtype=np.int32)
+    _load().bload_oracle_order(n, seed & (2**64 - 1), _p(out))
+    return out
+
+
+class Plan:
+    """Result of the next-fit plan."""
+
+    def __init__(self, order, block_of_seq, offset_of_seq, block_first, num_blocks,
+                 total_frames, t_blk):
+        self.order = order
+        self.block_of_seq = block_of_seq
+        self.offset_of_seq = offset_of_seq
+        self.block_first = block_first            # int32[num_blocks + 1]
+        self.num_blocks = num_blocks
+        self.total_frames = total_frames
+        self.t_blk = t_blk
+
+
+def plan(lengths, t_blk: int, order_) -> Plan:
+    """Next-fit over ``order_``; raises ValueError on a length outside [1, t_blk]."""
+    L = _c(lengths, np.int32)
+    o = _c(order_, np.int32)
+    n = L.shape[0]
+    assert o.shape[0] == n
+    block_of = np.full(n, -7, dtype=np.int32)
+    offset_of = np.full(n, -7, dtype=np.int32)
+    block_first = np.full(n + 1, -7, dtype=np.int32)
+    nb = np.zeros(1, dtype=np.int64)
+    tot = np.zeros(1, dtype=np.int64)
+    rc = _load().bload_oracle_plan(_p(L), n, t_blk, _p(o), _p(block_of), _p(offset_of),
+                                   _p(block_first), _p(nb), _p(tot))
+    if rc != 0:
+        raise ValueError("length outside [1, t_blk]")
+    b = int(nb[0])
+    return Plan(o, block_of, offset_of, block_first[:b + 1].copy() if n else block_first[:0],
+                b, int(tot[0]), t_blk)
+
+
+def pack_blocks(src, src_offsets, lengths, pl: Plan, frame_bytes: int, block_lo: int,
+                block_hi: int):
+    """Blocks [block_lo, block_hi) -> (packed u8[nb, T, frame_bytes], seq_id i32[nb, T],
+    frame_idx i32[nb, T], reset u8[nb, T], valid u8[nb, T])."""
+    src = np.ascontiguousarray(src)
+    src_b = src.view(np.uint8).reshape(-1)
+    so = _c(src_offsets, np.int64)
+    L = _c(lengths, np.int32)
+    n = L.shape[0]
+    assert src_b.shape[0] == int(so[-1]) * frame_bytes if n else True
+    nb = block_hi - block_lo
+    T = pl.t_blk
+    packed = np.full((nb, T, frame_bytes), 0xA5, dtype=np.uint8)
+    seq_id = np.full((nb, T), -9, dtype=np.int32)
+    frame_idx = np.full((nb, T), -9, dtype=np.int32)
+    reset = np.full((nb, T), 9, dtype=np.uint8)
+    valid = np.full((nb, T), 9, dtype=np.uint8)
+    _load().bload_oracle_pack_blocks(_p(src_b), _p(so), _p(L), _p(pl.block_of_seq),
+                                     _p(pl.offset_of_seq), n, T, frame_bytes, block_lo,
+                                     block_hi, _p(packed), _p(seq_id), _p(frame_idx),
+                                     _p(reset), _p(valid))
+    return packed, seq_id, frame_idx, reset, valid
+
+
+def pack(src, src_offsets, lengths, pl: Plan, frame_bytes: int):
+    return pack_blocks(src, src_offsets, lengths, pl, frame_bytes, 0, pl.num_blocks)
+
+
+def segment_reduce(src, src_offsets, lengths, feat_dim: int, dtype: str, op: str) -> np.ndarray:
+    """Per-sequence sum / mean over time of the ragged source ``[sum(L), feat_dim]``."""
+    src = np.ascontiguousarray(src, dtype=_NP_OF[dtype])
+    so = _c(src_offsets, np.int64)
+    L = _c(lengths, np.int32)
+    n = L.shape[0]
+    out = np.zeros((n, feat_dim), dtype=np.int64 if dtype == "i32" else np.float32)
+    rc = _load().bload_oracle_segment_reduce(_p(src), _p(so), _p(L), n, feat_dim,
+                                             DTYPE_CODE[dtype], OP_CODE[op], _p(out))
+    if rc != 0:
+        raise ValueError("unsupported dtype/op combination")
+    return out
+
+
+def padding(lengths, t_max: int, num_blocks: int, t_blk: int):
+    """(pad_longest, pad_blocks) in frames."""
+    L = _c(lengths, np.int32)
+    a = np.zeros(1, dtype=np.int64)
+    b = np.zeros(1, dtype=np.int64)
+    _load().bload_oracle_padding(_p(L), L.shape[0], t_max, num_blocks, t_blk, _p(a), _p(b))
+    return int(a[0]), int(b[0])

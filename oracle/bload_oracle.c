@@ -1,0 +1,264 @@
+/*
+ * CPU oracle for the BLoad block packer -- TEST INFRASTRUCTURE, not product.
+ *
+ * A plain, single-threaded, deliberately slow statement of what the packer
+ * computes, written from the paper (BLoad, arXiv 2310.10879) and used only to
+ * check the HIP library and to time a CPU baseline.  It shares no code with
+ * the HIP library and the library never calls it.
+ *
+ * What each function follows:
+ *   - order:   Methods section, "concatenating randomly sampled sequences":
+ *              the paper fixes no generator, so the random order is a keyed
+ *              bijection of [0, N) (balanced Feistel network + cycle walking,
+ *              Black & Rogaway 2002) whose round function is the MurmurHash3
+ *              32-bit finaliser and whose round keys are consecutive outputs
+ *              of SplitMix64 (Steele, Lea & Flood 2014) started at the seed.
+ *   - plan:    Methods section: blocks of T_max frames built from whole
+ *              sequences with T_i <= T_max, closed "as close to T_max" as the
+ *              running order allows (next-fit: a sequence that does not fit
+ *              the open block closes it and opens the next one).
+ *   - pack:    Methods section: the closed block is filled up with 0's; the
+ *              table "containing the starting index of each new video within
+ *              each particular block" is kept per sequence (offset) and per
+ *              frame slot (reset flag, sequence id, frame index, valid).
+ *   - reduce:  the consumer of that table (Methods section, resetting the
+ *              carried state where a new sequence starts), in its simplest
+ *              form: a per-sequence sum / mean over time.  Defined on the
+ *              ragged source, so it does not depend on plan or pack.
+ *   - padding: Problem Statement (padding every sample to the longest one)
+ *              and Table 1 ("padding amount").
+ *
+ * Parity pins (tests/test_oracle_*.py): SplitMix64 known answers, invertible
+ * finaliser, bijectivity and spread of the order; next-fit invariants, closed
+ * forms and a brute-force optimum on tiny inputs; frame-exactly-once decoding
+ * of a tagged payload; reductions of payloads with closed-form sums; the
+ * paper's printed pad-to-longest count.  The identity of the permutation (which
+ * bijection a seed gives) is a free choice of this build: "parity unpinned"
+ * beyond those properties.
+ */
+#include <stdint.h>
+#include <stddef.h>
+#include <string.h>
+#include <stdlib.h>
+
+/* ------------------------------------------------------------------ order */
+
+/* SplitMix64 output function. */
+static uint64_t oracle_mix64(uint64_t z)
+{
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
+/* k-th output (k = 0, 1, ...) of the SplitMix64 stream whose state starts at
+ * `seed`: the state advances by the golden-ratio increment before each output. */
+uint64_t bload_oracle_splitmix64(uint64_t seed, uint64_t k)
+{
+    return oracle_mix64(seed + (k + 1) * 0x9E3779B97F4A7C15ULL);
+}
+
+/* MurmurHash3 32-bit finaliser. */
+uint32_t bload_oracle_fmix32(uint32_t h)
+{
+    h ^= h >> 16;
+    h *= 0x85EBCA6BU;
+    h ^= h >> 13;
+    h *= 0xC2B2AE35U;
+    h ^= h >> 16;
+    return h;
+}
+
+#define ORACLE_FEISTEL_ROUNDS 6
+
+/* One pass of the 6-round balanced Feistel network over 2*half_bits bits. */
+static uint32_t oracle_feistel(uint32_t x, int half_bits, const uint32_t* key)
+{
+    uint32_t mask = ((uint32_t)1 << half_bits) - 1U;
+    uint32_t left = x >> half_bits;
+    uint32_t right = x & mask;
+    for (int r = 0; r < ORACLE_FEISTEL_ROUNDS; ++r) {
+        uint32_t f = bload_oracle_fmix32(right + key[r]) & mask;
+        uint32_t new_right = left ^ f;
+        left = right;
+        right = new_right;
+    }
+    return (left << half_bits) | right;
+}
+
+/* order[p] = index of the sequence at shuffled position p. */
+void bload_oracle_order(int64_t n, uint64_t seed, int32_t* order)
+{
+    if (n <= 0) return;
+    if (n == 1) { order[0] = 0; return; }
+    /* smallest even bit width whose domain holds [0, n) */
+    int width = 0;
+    while (((uint64_t)1 << width) < (uint64_t)n) ++width;
+    if (width < 2) width = 2;
+    if (width & 1) ++width;
+    int half_bits = width / 2;
+    uint32_t key[ORACLE_FEISTEL_ROUNDS];
+    for (int r = 0; r < ORACLE_FEISTEL_ROUNDS; ++r)
+        key[r] = (uint32_t)bload_oracle_splitmix64(seed, (uint64_t)r);
+    for (int64_t p = 0; p < n; ++p) {
+        uint32_t y = oracle_feistel((uint32_t)p, half_bits, key);
+        while ((uint64_t)y >= (uint64_t)n)          /* cycle walking */
+            y = oracle_feistel(y, half_bits, key);
+        order[p] = (int32_t)y;
+    }
+}
+
+/* ------------------------------------------------------------------- plan */
+
+/* Next-fit over the sequences taken in `order`.
+ * Returns 0, or 2 if some length is < 1 or > t_blk (then outputs are undefined).
+ * block_first has room for n+1 entries; entries [0 .. B] are written. */
+int bload_oracle_plan(const int32_t* lengths, int64_t n, int32_t t_blk,
+                      const int32_t* order,
+                      int32_t* block_of_seq, int32_t* offset_of_seq,
+                      int32_t* block_first,
+                      int64_t* num_blocks, int64_t* total_frames)
+{
+    *num_blocks = 0;
+    *total_frames = 0;
+    for (int64_t i = 0; i < n; ++i)
+        if (lengths[i] < 1 || lengths[i] > t_blk) return 2;
+    if (n <= 0) return 0;
+    int64_t b = 0;
+    int64_t fill = 0;
+    int64_t total = 0;
+    block_first[0] = 0;
+    for (int64_t p = 0; p < n; ++p) {
+        int32_t i = order[p];
+        int64_t len = lengths[i];
+        if (fill + len > (int64_t)t_blk) {   /* does not fit: close, open next */
+            b += 1;
+            fill = 0;
+            block_first[b] = (int32_t)p;
+        }
+        block_of_seq[i] = (int32_t)b;
+        offset_of_seq[i] = (int32_t)fill;
+        fill += len;
+        total += len;
+    }
+    block_first[b + 1] = (int32_t)n;
+    *num_blocks = b + 1;
+    *total_frames = total;
+    return 0;
+}
+
+/* ------------------------------------------------------------------- pack */
+
+/* Blocks [block_lo, block_hi) of the packed tensor and of the four metadata
+ * planes; every output pointer addresses the slab's first slot, i.e. slot
+ * (block_lo, 0).  Padding: payload bytes 0, seq_id = frame_idx = -1,
+ * reset = valid = 0. */
+void bload_oracle_pack_blocks(const uint8_t* src, const int64_t* src_offsets,
+                              const int32_t* lengths,
+                              const int32_t* block_of_seq, const int32_t* offset_of_seq,
+                              int64_t n, int32_t t_blk, int64_t frame_bytes,
+                              int64_t block_lo, int64_t block_hi,
+                              uint8_t* packed, int32_t* seq_id, int32_t* frame_idx,
+                              uint8_t* reset, uint8_t* valid)
+{
+    int64_t slots = (block_hi - block_lo) * (int64_t)t_blk;
+    if (slots <= 0) return;
+    memset(packed, 0, (size_t)(slots * frame_bytes));
+    for (int64_t s = 0; s < slots; ++s) {
+        seq_id[s] = -1;
+        frame_idx[s] = -1;
+        reset[s] = 0;
+        valid[s] = 0;
+    }
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t b = block_of_seq[i];
+        if (b < block_lo || b >= block_hi) continue;
+        for (int64_t t = 0; t < lengths[i]; ++t) {
+            int64_t s = (b - block_lo) * (int64_t)t_blk + offset_of_seq[i] + t;
+            memcpy(packed + s * frame_bytes,
+                   src + (src_offsets[i] + t) * frame_bytes, (size_t)frame_bytes);
+            seq_id[s] = (int32_t)i;
+            frame_idx[s] = (int32_t)t;
+            reset[s] = (uint8_t)(t == 0);
+            valid[s] = 1;
+        }
+    }
+}
+
+/* ----------------------------------------------------------------- reduce */
+
+/* IEEE binary16 bit pattern -> double (exact). */
+double bload_oracle_half_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int expo = (h >> 10) & 0x1F;
+    int frac = h & 0x3FF;
+    double v;
+    if (expo == 0) {
+        v = (double)frac * (1.0 / 16777216.0);              /* frac * 2^-24 */
+    } else if (expo == 31) {
+        if (frac == 0) v = 1.0 / 0.0; else v = 0.0 / 0.0;
+    } else {
+        v = 1.0 + (double)frac * (1.0 / 1024.0);
+        int e = expo - 15;
+        while (e > 0) { v *= 2.0; --e; }
+        while (e < 0) { v *= 0.5; ++e; }
+    }
+    return sign ? -v : v;
+}
+
+/* dtype: 0 = u8, 1 = f16, 2 = f32, 3 = i32.   op: 0 = sum, 1 = mean.
+ * out is float[n, feat_dim] for dtypes 0..2 (accumulated in double, rounded
+ * once), int64[n, feat_dim] for i32 (exact; mean = sum / L truncated toward
+ * zero is not defined by the build and is refused by returning 1). */
+int bload_oracle_segment_reduce(const void* src, const int64_t* src_offsets,
+                                const int32_t* lengths, int64_t n, int64_t feat_dim,
+                                int dtype, int op, void* out)
+{
+    if (dtype == 3 && op != 0) return 1;
+    if (n <= 0 || feat_dim <= 0) return 0;
+    /* one accumulator per feature; frames are added in time order */
+    double* acc = (double*)malloc((size_t)feat_dim * sizeof(double));
+    int64_t* iacc = (int64_t*)malloc((size_t)feat_dim * sizeof(int64_t));
+    if (!acc || !iacc) { free(acc); free(iacc); return 3; }
+    for (int64_t i = 0; i < n; ++i) {
+        for (int64_t d = 0; d < feat_dim; ++d) { acc[d] = 0.0; iacc[d] = 0; }
+        for (int64_t t = 0; t < lengths[i]; ++t) {
+            int64_t base = (src_offsets[i] + t) * feat_dim;
+            for (int64_t d = 0; d < feat_dim; ++d) {
+                int64_t e = base + d;
+                if (dtype == 0) acc[d] += (double)((const uint8_t*)src)[e];
+                else if (dtype == 1) acc[d] += bload_oracle_half_to_double(((const uint16_t*)src)[e]);
+                else if (dtype == 2) acc[d] += (double)((const float*)src)[e];
+                else iacc[d] += (int64_t)((const int32_t*)src)[e];
+            }
+        }
+        for (int64_t d = 0; d < feat_dim; ++d) {
+            if (dtype == 3) {
+                ((int64_t*)out)[i * feat_dim + d] = iacc[d];
+            } else {
+                double v = acc[d];
+                if (op == 1) v /= (double)lengths[i];
+                ((float*)out)[i * feat_dim + d] = (float)v;
+            }
+        }
+    }
+    free(acc);
+    free(iacc);
+    return 0;
+}
+
+/* ---------------------------------------------------------------- padding */
+
+/* Padding counts, in frames:
+ *   pad_longest = N * t_max - sum(L)        (every sample padded to t_max)
+ *   pad_blocks  = num_blocks * t_blk - sum(L)  (block packing) */
+void bload_oracle_padding(const int32_t* lengths, int64_t n, int64_t t_max,
+                          int64_t num_blocks, int64_t t_blk,
+                          int64_t* pad_longest, int64_t* pad_blocks)
+{
+    int64_t total = 0;
+    for (int64_t i = 0; i < n; ++i) total += lengths[i];
+    *pad_longest = n * t_max - total;
+    *pad_blocks = num_blocks * t_blk - total;
+}
