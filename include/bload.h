@@ -1,0 +1,171 @@
+/*
+ * bload.h -- C ABI of the BLoad block packer for MI355X (gfx950).
+ *
+ * BLoad (arXiv 2310.10879) trains on N sequences S_i of H x W x T_i frames
+ * with varying T_i (Problem Statement) by concatenating randomly ordered whole
+ * sequences into blocks of a fixed length T_blk = T_max, padding each block's
+ * tail with 0's, and keeping a table of where each sequence starts inside its
+ * block so that a recurrent consumer can reset its carried state there
+ * (Methods).  This library is that packer, on the GPU:
+ *
+ *   bload_plan            order the sequences by seed and assign them to blocks
+ *   bload_pack            gather the frames into [num_blocks, T_blk, frame] and
+ *                         write the per-slot form of the start table
+ *   bload_segment_reduce  per-sequence sum / mean over the packed blocks, using
+ *                         only the packed tensor and that per-slot table
+ *
+ * Conventions
+ *   - Pointers named d_* are DEVICE pointers (hipMalloc-style memory of the
+ *     current device), h_* are HOST pointers.  The caller owns every buffer;
+ *     the library allocates nothing and keeps no state between calls.
+ *   - A frame is an opaque record of `frame_bytes` bytes (H*W*C*sizeof(elem));
+ *     H and W are the same for all sequences of one call.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     bload_pack and bload_segment_reduce only enqueue work on it;
+ *     bload_plan enqueues, then waits for the stream, because it returns the
+ *     block count to the host.
+ *   - Every function returns a bload_status; nothing is thrown.  On any
+ *     status other than BLOAD_OK the contents of the output buffers are
+ *     unspecified (but nothing outside them is ever written).
+ *   - Sizes: 0 <= n_seq <= BLOAD_MAX_SEQ, 1 <= t_blk, 1 <= L_i <= t_blk,
+ *     num_blocks * t_blk < 2^40 slots.
+ */
+#ifndef BLOAD_H
+#define BLOAD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BLOAD_MAX_SEQ ((int64_t)1 << 27)
+
+typedef enum {
+    BLOAD_OK = 0,
+    BLOAD_EINVAL = 1,      /* null pointer, negative size, t_blk < 1, frame_bytes < 1,
+                              unknown dtype / op, or an unsupported dtype-op pair */
+    BLOAD_ELENGTH = 2,     /* some L_i < 1 or L_i > t_blk (the method needs T_i <= T_max) */
+    BLOAD_EWORKSPACE = 3,  /* workspace smaller than the *_workspace_bytes() answer */
+    BLOAD_EALIGN = 4,      /* a payload / workspace base is not 16-byte aligned, or an
+                              int32 / int64 table is not naturally aligned */
+    BLOAD_EOVERFLOW = 5,   /* n_seq or num_blocks * t_blk beyond the supported range */
+    BLOAD_EHIP = 6         /* a HIP runtime call failed (bload_last_hip_error() says which) */
+} bload_status;
+
+typedef enum { BLOAD_U8 = 0, BLOAD_F16 = 1, BLOAD_F32 = 2, BLOAD_I32 = 3 } bload_dtype;
+typedef enum { BLOAD_SUM = 0, BLOAD_MEAN = 1 } bload_op;
+
+/* Human-readable name of a status (static storage, never NULL). */
+const char* bload_status_string(bload_status status);
+
+/* hipError_t (as int) of the most recent failing HIP call made by this library
+ * on the calling thread, 0 if none. */
+int bload_last_hip_error(void);
+
+/* ------------------------------------------------------------------ plan --
+ * Methods section: "blocks of size T_max by concatenating randomly sampled
+ * sequences with length T_i <= T_max", each block closed as near T_max as the
+ * visiting order allows, plus the table of starting indices.
+ *
+ * order:  a permutation of [0, n_seq) fixed by `seed` alone: position p holds
+ *         the sequence walk(p), where walk applies a 6-round balanced Feistel
+ *         network over the smallest even bit width w >= 2 with 2^w >= n_seq
+ *         (round function: MurmurHash3's 32-bit finaliser of right-half +
+ *         key_r, masked to w/2 bits; key_r = low 32 bits of the r-th output of
+ *         SplitMix64 started at `seed`) and re-applies it until the value is
+ *         below n_seq.  n_seq <= 1 gives the identity.
+ * assign: next-fit over that order: a sequence goes into the open block if
+ *         fill + L <= t_blk, otherwise the block is closed (its tail is
+ *         padding) and the sequence opens the next one.
+ *
+ * d_lengths        in   int32[n_seq]   L_i, in original sequence order
+ * d_order          out  int32[n_seq]   order[p] = sequence at shuffled position p
+ * d_block_of_seq   out  int32[n_seq]   block of sequence i      (original index)
+ * d_offset_of_seq  out  int32[n_seq]   first slot of sequence i inside its block
+ *                                      (the paper's start table, per sequence)
+ * d_block_first    out  int32[n_seq+1] capacity; entries [0 .. B] are written:
+ *                                      first shuffled position of block b, [B] = n_seq
+ * h_num_blocks     out  host int64     B
+ * h_total_frames   out  host int64     sum of L_i
+ * d_workspace           device scratch of >= bload_plan_workspace_bytes(n_seq)
+ *                       bytes, 16-byte aligned; contents meaningless afterwards
+ *
+ * Lengths are checked on the device; a bad one gives BLOAD_ELENGTH.  n_seq = 0
+ * gives B = 0, BLOAD_OK, and writes nothing to the device.  Synchronises the
+ * stream before returning.
+ */
+size_t bload_plan_workspace_bytes(int64_t n_seq);
+
+bload_status bload_plan(const int32_t* d_lengths, int64_t n_seq, int32_t t_blk, uint64_t seed,
+                        int32_t* d_order, int32_t* d_block_of_seq, int32_t* d_offset_of_seq,
+                        int32_t* d_block_first,
+                        int64_t* h_num_blocks, int64_t* h_total_frames,
+                        void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------ pack --
+ * Methods section: the sequences of a block are laid one after another and the
+ * rest of the block is filled with 0's; the start table says where each new
+ * sequence begins.
+ *
+ * d_src          in   bytes[total_frames * frame_bytes]: the ragged source, the
+ *                     frames of sequence i stored contiguously from frame
+ *                     d_src_offsets[i]; 16-byte aligned when frame_bytes % 16 == 0,
+ *                     else aligned to the largest power of two <= 8 dividing frame_bytes
+ * d_src_offsets  in   int64[n_seq+1]  first source frame of each sequence;
+ *                     src_offsets[i+1] - src_offsets[i] must equal L_i (not checked)
+ * d_lengths, d_order, d_block_of_seq, d_offset_of_seq, d_block_first
+ *                in   as produced by bload_plan for the same lengths
+ * num_blocks     in   B as returned by bload_plan
+ * d_packed       out  bytes[B, t_blk, frame_bytes], 16-byte aligned; slot
+ *                     (b, offset_of_seq[i] + t) receives frame t of sequence i,
+ *                     every other byte is 0
+ * d_seq_id       out  int32[B, t_blk]  original sequence index, -1 on padding
+ * d_frame_idx    out  int32[B, t_blk]  frame number inside its sequence, -1 on padding
+ * d_reset        out  uint8[B, t_blk]  1 on the first frame of a sequence, else 0
+ * d_valid        out  uint8[B, t_blk]  1 on a real frame, 0 on padding
+ *
+ * Every byte of the five outputs is written exactly once (no prior memset is
+ * needed).  Asynchronous on `hip_stream`.  n_seq = 0 / num_blocks = 0: no-op.
+ */
+bload_status bload_pack(const void* d_src, const int64_t* d_src_offsets, const int32_t* d_lengths,
+                        const int32_t* d_order, const int32_t* d_block_of_seq,
+                        const int32_t* d_offset_of_seq, const int32_t* d_block_first,
+                        int64_t n_seq, int64_t num_blocks, int32_t t_blk, int64_t frame_bytes,
+                        void* d_packed, int32_t* d_seq_id, int32_t* d_frame_idx,
+                        uint8_t* d_reset, uint8_t* d_valid, void* hip_stream);
+
+/* -------------------------------------------------------- segment reduce --
+ * Methods section: knowing where a new sequence starts lets the consumer drop
+ * what it carried from the previous frame.  The simplest such consumer: a
+ * running sum over time that is restarted at every start flag and never
+ * crosses a block boundary.  It receives no plan tables: segments are found
+ * from d_reset / d_valid alone, d_seq_id only names the output row.
+ *
+ * d_packed   in   [B, t_blk, feat_dim] of `dtype`, 16-byte aligned
+ * d_seq_id   in   int32[B, t_blk];  d_reset, d_valid in uint8[B, t_blk]
+ * d_out      out  [n_seq, feat_dim]: float32 for U8 / F16 / F32 inputs (float32
+ *                 accumulation over chunks of time, chunks added in time order),
+ *                 int64 for I32 (exact).  MEAN divides by the segment's frame
+ *                 count; I32 supports SUM only.  Row i is written iff some
+ *                 valid segment carries seq_id i; ids outside [0, n_seq) are
+ *                 skipped.
+ * d_workspace     device scratch of >= bload_segment_reduce_workspace_bytes(...)
+ *                 bytes, 16-byte aligned.
+ *
+ * Asynchronous on `hip_stream`; same inputs give bit-identical outputs.
+ */
+size_t bload_segment_reduce_workspace_bytes(int64_t num_blocks, int32_t t_blk, int64_t feat_dim,
+                                            bload_dtype dtype);
+
+bload_status bload_segment_reduce(const void* d_packed, const int32_t* d_seq_id,
+                                  const uint8_t* d_reset, const uint8_t* d_valid,
+                                  int64_t num_blocks, int32_t t_blk, int64_t feat_dim,
+                                  bload_dtype dtype, bload_op op, int64_t n_seq, void* d_out,
+                                  void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BLOAD_H */

@@ -1,0 +1,200 @@
+"""Python binding of the BLoad C-ABI library (``include/bload.h``).
+
+Argument marshalling only: every function here checks dtypes / devices, takes
+``data_ptr()`` of torch tensors (torch is used for device memory and streams,
+nothing else) and calls the entry point of the same name in ``libbload.so``.
+There is no fallback: importing this module without the built library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbload.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_2310_10879_amd.build` "
+        "(there is no CPU fallback)")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+# status codes (mirror of bload_status)
+OK, EINVAL, ELENGTH, EWORKSPACE, EALIGN, EOVERFLOW, EHIP = range(7)
+DTYPES = {"u8": 0, "f16": 1, "f32": 2, "i32": 3}
+OPS = {"sum": 0, "mean": 1}
+TORCH_DTYPE = {"u8": torch.uint8, "f16": torch.float16, "f32": torch.float32, "i32": torch.int32}
+MAX_SEQ = 1 << 27
+
+_vp, _i64, _i32, _u64, _sz = (ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64,
+                              ctypes.c_size_t)
+
+_lib.bload_status_string.restype = ctypes.c_char_p
+_lib.bload_status_string.argtypes = [ctypes.c_int]
+_lib.bload_last_hip_error.restype = ctypes.c_int
+_lib.bload_last_hip_error.argtypes = []
+_lib.bload_plan_workspace_bytes.restype = _sz
+_lib.bload_plan_workspace_bytes.argtypes = [_i64]
+_lib.bload_plan.restype = ctypes.c_int
+_lib.bload_plan.argtypes = [_vp, _i64, _i32, _u64, _vp, _vp, _vp, _vp,
+                            ctypes.POINTER(_i64), ctypes.POINTER(_i64), _vp, _sz, _vp]
+_lib.bload_pack.restype = ctypes.c_int
+_lib.bload_pack.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i32, _i64,
+                            _vp, _vp, _vp, _vp, _vp, _vp]
+if hasattr(_lib, "bload_segment_reduce"):
+  _lib.bload_segment_reduce_workspace_bytes.restype = _sz
+  _lib.bload_segment_reduce_workspace_bytes.argtypes = [_i64, _i32, _i64, ctypes.c_int]
+  _lib.bload_segment_reduce.restype = ctypes.c_int
+  _lib.bload_segment_reduce.argtypes = [_vp, _vp, _vp, _vp, _i64, _i32, _i64, ctypes.c_int,
+                                      ctypes.c_int, _i64, _vp, _vp, _sz, _vp]
+
+
+class BloadError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        msg = _lib.bload_status_string(status).decode()
+        if status == EHIP:
+            msg += f" (hipError {_lib.bload_last_hip_error()})"
+        super().__init__(msg)
+
+
+def status_string(status: int) -> str:
+    return _lib.bload_status_string(status).decode()
+
+
+def _check(status: int) -> None:
+    if status != OK:
+        raise BloadError(status)
+
+
+def _ptr(t, dtype=None) -> int:
+    if t is None:
+        return 0
+    if not t.is_cuda:
+        raise ValueError("expected a device tensor")
+    if not t.is_contiguous():
+        raise ValueError("expected a contiguous tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"expected {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def bload_plan_workspace_bytes(n_seq: int) -> int:
+    return int(_lib.bload_plan_workspace_bytes(n_seq))
+
+
+def bload_segment_reduce_workspace_bytes(num_blocks: int, t_blk: int, feat_dim: int,
+                                         dtype: str) -> int:
+    return int(_lib.bload_segment_reduce_workspace_bytes(num_blocks, t_blk, feat_dim,
+                                                         DTYPES[dtype]))
+
+
+@dataclass
+class Plan:
+    """Device-resident result of ``bload_plan``."""
+    order: torch.Tensor            # int32[N]
+    block_of_seq: torch.Tensor     # int32[N]
+    offset_of_seq: torch.Tensor    # int32[N]
+    block_first: torch.Tensor      # int32[N+1], entries [0..B] valid
+    num_blocks: int
+    total_frames: int
+    t_blk: int
+
+
+def bload_plan(lengths: torch.Tensor, t_blk: int, seed: int, workspace: torch.Tensor | None = None,
+               out: Plan | None = None) -> Plan:
+    """lengths: int32[N] on the device.  Synchronises the current stream."""
+    n = lengths.shape[0]
+    dev = lengths.device
+    if out is None:
+        out = Plan(torch.empty(n, dtype=torch.int32, device=dev),
+                   torch.empty(n, dtype=torch.int32, device=dev),
+                   torch.empty(n, dtype=torch.int32, device=dev),
+                   torch.empty(n + 1, dtype=torch.int32, device=dev), 0, 0, t_blk)
+    need = bload_plan_workspace_bytes(n)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    nb, tot = _i64(0), _i64(0)
+    st = _lib.bload_plan(_ptr(lengths, torch.int32), n, t_blk, seed & (2**64 - 1),
+                         _ptr(out.order, torch.int32), _ptr(out.block_of_seq, torch.int32),
+                         _ptr(out.offset_of_seq, torch.int32), _ptr(out.block_first, torch.int32),
+                         ctypes.byref(nb), ctypes.byref(tot), _ptr(workspace),
+                         workspace.numel() * workspace.element_size(), _stream())
+    _check(st)
+    out.num_blocks, out.total_frames, out.t_blk = int(nb.value), int(tot.value), t_blk
+    return out
+
+
+@dataclass
+class Packed:
+    """Device-resident result of ``bload_pack``."""
+    packed: torch.Tensor      # uint8[B, T, frame_bytes]
+    seq_id: torch.Tensor      # int32[B, T]
+    frame_idx: torch.Tensor   # int32[B, T]
+    reset: torch.Tensor       # uint8[B, T]
+    valid: torch.Tensor       # uint8[B, T]
+
+
+def alloc_packed(num_blocks: int, t_blk: int, frame_bytes: int, device) -> Packed:
+    return Packed(torch.empty((num_blocks, t_blk, frame_bytes), dtype=torch.uint8, device=device),
+                  torch.empty((num_blocks, t_blk), dtype=torch.int32, device=device),
+                  torch.empty((num_blocks, t_blk), dtype=torch.int32, device=device),
+                  torch.empty((num_blocks, t_blk), dtype=torch.uint8, device=device),
+                  torch.empty((num_blocks, t_blk), dtype=torch.uint8, device=device))
+
+
+def bload_pack(src: torch.Tensor, src_offsets: torch.Tensor, lengths: torch.Tensor, plan: Plan,
+               frame_bytes: int, out: Packed | None = None) -> Packed:
+    """src: the ragged source (any dtype, contiguous, ``total_frames * frame_bytes`` bytes);
+    src_offsets: int64[N+1].  Asynchronous on the current stream."""
+    n = lengths.shape[0]
+    if src.numel() * src.element_size() != plan.total_frames * frame_bytes:
+        raise ValueError("source size does not match total_frames * frame_bytes")
+    if out is None:
+        out = alloc_packed(plan.num_blocks, plan.t_blk, frame_bytes, lengths.device)
+    if out.packed.numel() != plan.num_blocks * plan.t_blk * frame_bytes or \
+            out.seq_id.numel() != plan.num_blocks * plan.t_blk:
+        raise ValueError("output buffers do not match num_blocks * t_blk")
+    st = _lib.bload_pack(_ptr(src), _ptr(src_offsets, torch.int64), _ptr(lengths, torch.int32),
+                         _ptr(plan.order, torch.int32), _ptr(plan.block_of_seq, torch.int32),
+                         _ptr(plan.offset_of_seq, torch.int32), _ptr(plan.block_first, torch.int32),
+                         n, plan.num_blocks, plan.t_blk, frame_bytes,
+                         _ptr(out.packed, torch.uint8), _ptr(out.seq_id, torch.int32),
+                         _ptr(out.frame_idx, torch.int32), _ptr(out.reset, torch.uint8),
+                         _ptr(out.valid, torch.uint8), _stream())
+    _check(st)
+    return out
+
+
+def bload_segment_reduce(packed: torch.Tensor, seq_id: torch.Tensor, reset: torch.Tensor,
+                         valid: torch.Tensor, num_blocks: int, t_blk: int, feat_dim: int,
+                         dtype: str, op: str, n_seq: int, out: torch.Tensor | None = None,
+                         workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Per-sequence sum / mean over the packed blocks -> [n_seq, feat_dim] (float32, or int64
+    for ``i32``).  Rows of sequences that do not occur keep their previous content (zeros when
+    this function allocates ``out``).  Asynchronous on the current stream."""
+    dev = packed.device
+    if out is None:
+        out = torch.zeros((n_seq, feat_dim), device=dev,
+                          dtype=torch.int64 if dtype == "i32" else torch.float32)
+    need = bload_segment_reduce_workspace_bytes(num_blocks, t_blk, feat_dim, dtype)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    esize = torch.empty(0, dtype=TORCH_DTYPE[dtype]).element_size()
+    if packed.numel() * packed.element_size() != num_blocks * t_blk * feat_dim * esize:
+        raise ValueError("packed size does not match num_blocks * t_blk * feat_dim")
+    st = _lib.bload_segment_reduce(_ptr(packed), _ptr(seq_id, torch.int32),
+                                   _ptr(reset, torch.uint8), _ptr(valid, torch.uint8),
+                                   num_blocks, t_blk, feat_dim, DTYPES[dtype], OPS[op], n_seq,
+                                   _ptr(out), _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream())
+    _check(st)
+    return out

@@ -1,0 +1,443 @@
+// bload_pack: gather the frames of every sequence into the dense
+// [num_blocks, T_blk, frame] tensor, fill the rest with 0's, and write the
+// per-slot form of the start table (BLoad, Methods section).
+//
+// The kernels are destination driven: a workgroup owns a contiguous piece of
+// the packed tensor (a "tile"), looks up which sequences land in it, stages
+// that short index table in LDS, and then streams 16-byte vectors from the
+// ragged source to the tile.  Every output byte is written by exactly one
+// thread, so no memset pass and no atomics are needed.
+//
+// Two tile shapes:
+//   wide   (frame_bytes >= 256): a tile is a flat byte range of the packed
+//          tensor; each sequence overlapping it is one long contiguous copy.
+//   narrow (frame_bytes <  256): a tile is 1024 consecutive slots; lanes take
+//          consecutive 16-byte destination vectors and assemble them from
+//          source elements of the widest type that divides the frame.
+#include "bload_common.hpp"
+
+#include <limits.h>
+
+namespace bload {
+
+struct PackArgs {
+    const uint8_t* src;
+    const int64_t* src_offsets;
+    const int32_t* lengths;
+    const int32_t* order;
+    const int32_t* block_of_seq;
+    const int32_t* offset_of_seq;
+    const int32_t* block_first;
+    int32_t n_seq;
+    int32_t t_blk;
+    int64_t frame_bytes;
+    int64_t total_slots;      // num_blocks * t_blk
+    uint8_t* packed;
+    int32_t* seq_id;
+    int32_t* frame_idx;
+    uint8_t* reset;
+    uint8_t* valid;
+};
+
+// The sequences ("runs") that overlap one tile, in shuffled order.  Slots are
+// numbered globally (block * T_blk + slot in block); dst is relative to the
+// tile's first slot and is negative for a run that starts before the tile.
+template <int MAXRUNS>
+struct RunTable {
+    int64_t src[MAXRUNS];      // first source frame of the run
+    int32_t dst[MAXRUNS + 1];  // first slot, tile relative; [n] = INT_MAX sentinel
+    int32_t len[MAXRUNS];      // frames in the run
+    int32_t seq[MAXRUNS];      // original sequence index
+    int32_t n;
+};
+
+// Fill `tab` with the runs overlapping global slots [gs_lo, gs_hi).  Called by
+// one whole wave; the caller puts a barrier after it.
+//
+// Runs are sorted by destination in shuffled order, so the first overlapping
+// run is found by a 64-way search over the positions of the tile's first
+// block, then the table is read forward 64 positions at a time.
+template <int MAXRUNS>
+__device__ __forceinline__ void find_runs(const PackArgs& a, int64_t gs_lo, int64_t gs_hi,
+                                          RunTable<MAXRUNS>& tab)
+{
+    const int lane = lane_id();
+    const int32_t n_seq = a.n_seq;
+    const int64_t t_blk = a.t_blk;
+    const int64_t b0 = gs_lo / t_blk;
+    const int32_t rel = (int32_t)(gs_lo - b0 * t_blk);       // slot inside block b0
+
+    int32_t lo = min(max(a.block_first[b0], 0), n_seq);
+    int32_t hi = min(max(a.block_first[b0 + 1], lo), n_seq);
+    // A = first position p in [lo, hi) whose sequence ends after slot `rel` of
+    // block b0 (ends grow with p); hi if there is none.
+    while (hi - lo > kWave) {
+        const int32_t step = (hi - lo + kWave - 1) / kWave;
+        const int32_t q = lo + lane * step;
+        bool ends_after = true;
+        if (q < hi) {
+            const uint32_t i = (uint32_t)a.order[q];
+            ends_after = i >= (uint32_t)n_seq ||
+                         (int64_t)a.offset_of_seq[i] + a.lengths[i] > rel;
+        }
+        const uint64_t vote = __ballot(ends_after);
+        const int first = vote ? __ffsll((unsigned long long)vote) - 1 : kWave;
+        if (first == 0) { hi = lo; break; }
+        const int32_t probe_hit = lo + first * step;             // only meaningful if first < 64
+        lo = lo + (first - 1) * step + 1;
+        if (first < kWave && probe_hit < hi) hi = probe_hit;
+    }
+    {
+        const int32_t q = lo + lane;
+        bool ends_after = true;
+        if (q < hi) {
+            const uint32_t i = (uint32_t)a.order[q];
+            ends_after = i >= (uint32_t)n_seq ||
+                         (int64_t)a.offset_of_seq[i] + a.lengths[i] > rel;
+        }
+        const uint64_t vote = __ballot(ends_after);
+        lo += vote ? __ffsll((unsigned long long)vote) - 1 : kWave;
+    }
+
+    int n = 0;
+    for (int32_t base = lo; base < n_seq && n < MAXRUNS; base += kWave) {
+        const int32_t q = base + lane;
+        bool take = false;
+        int64_t src = 0;
+        int32_t dst = 0, len = 0, seq = 0;
+        if (q < n_seq) {
+            const uint32_t i = (uint32_t)a.order[q];
+            if (i < (uint32_t)n_seq) {
+                const int64_t g = (int64_t)a.block_of_seq[i] * t_blk + a.offset_of_seq[i];
+                take = g < gs_hi;
+                if (take) {
+                    dst = (int32_t)(g - gs_lo);
+                    len = a.lengths[i];
+                    seq = (int32_t)i;
+                    src = a.src_offsets[i];
+                }
+            }
+        }
+        // runs are sorted by destination: the takers are the leading lanes
+        const uint64_t refuse = ~__ballot(take);
+        const int cnt = refuse ? __ffsll((unsigned long long)refuse) - 1 : kWave;
+        if (lane < cnt && n + lane < MAXRUNS) {
+            tab.src[n + lane] = src;
+            tab.dst[n + lane] = dst;
+            tab.len[n + lane] = len;
+            tab.seq[n + lane] = seq;
+        }
+        n += cnt;
+        if (cnt < kWave) break;
+    }
+    n = min(n, MAXRUNS);
+    if (lane == 0) {
+        tab.n = n;
+        tab.dst[n] = INT_MAX;
+    }
+}
+
+// Index of the last run whose first slot is <= slot (tile relative), -1 if none.
+template <int MAXRUNS>
+__device__ __forceinline__ int run_of_slot(const RunTable<MAXRUNS>& tab, int n, int32_t slot)
+{
+    int lo = 0, hi = n;                 // first run with dst > slot
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (tab.dst[mid] <= slot) lo = mid + 1; else hi = mid;
+    }
+    return lo - 1;
+}
+
+// ------------------------------------------------------------------- wide
+
+constexpr int kWideTileMax = 65536;                 // bytes of packed tensor per workgroup
+constexpr int kWideMinFrame = 256;                  // smallest frame the wide kernel takes
+constexpr int kWideMaxRuns = kWideTileMax / kWideMinFrame + 2;
+
+typedef vec16 __attribute__((aligned(1))) vec16_unaligned;
+
+// Write packed bytes [lo, hi): copies of src[0 ..) (any alignment) or zeros.
+// Destination vectors are 16-byte aligned; the ragged ends of the range are
+// written byte by byte.  Called by all threads of the workgroup.
+template <bool ZERO>
+__device__ __forceinline__ void write_range(uint8_t* packed, int64_t lo, int64_t hi,
+                                            const uint8_t* src)
+{
+    const int tid = (int)threadIdx.x;
+    int64_t lo_al = (lo + 15) & ~(int64_t)15;
+    if (lo_al > hi) lo_al = hi;
+    int64_t hi_al = hi & ~(int64_t)15;
+    if (hi_al < lo_al) hi_al = lo_al;
+    const int head = (int)(lo_al - lo);
+    const int tail = (int)(hi - hi_al);
+    if (tid < head) packed[lo + tid] = ZERO ? (uint8_t)0 : src[tid];
+    if (tid >= kWave && tid - kWave < tail)
+        packed[hi_al + (tid - kWave)] = ZERO ? (uint8_t)0 : src[(hi_al - lo) + (tid - kWave)];
+
+    const int nv = (int)((hi_al - lo_al) >> 4);
+    vec16* d = reinterpret_cast<vec16*>(packed + lo_al);
+    const uint8_t* s = src + (lo_al - lo);
+    int v = tid;
+    if (ZERO) {
+        const vec16 z = {0u, 0u, 0u, 0u};
+        for (; v < nv; v += kThreads) store_stream(d + v, z);
+    } else {
+        for (; v + 3 * kThreads < nv; v += 4 * kThreads) {
+            const vec16 x0 = __builtin_nontemporal_load(
+                reinterpret_cast<const vec16_unaligned*>(s + 16 * (int64_t)v));
+            const vec16 x1 = __builtin_nontemporal_load(
+                reinterpret_cast<const vec16_unaligned*>(s + 16 * (int64_t)(v + kThreads)));
+            const vec16 x2 = __builtin_nontemporal_load(
+                reinterpret_cast<const vec16_unaligned*>(s + 16 * (int64_t)(v + 2 * kThreads)));
+            const vec16 x3 = __builtin_nontemporal_load(
+                reinterpret_cast<const vec16_unaligned*>(s + 16 * (int64_t)(v + 3 * kThreads)));
+            store_stream(d + v, x0);
+            store_stream(d + v + kThreads, x1);
+            store_stream(d + v + 2 * kThreads, x2);
+            store_stream(d + v + 3 * kThreads, x3);
+        }
+        for (; v < nv; v += kThreads) {
+            const vec16 x = __builtin_nontemporal_load(
+                reinterpret_cast<const vec16_unaligned*>(s + 16 * (int64_t)v));
+            store_stream(d + v, x);
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void pack_wide_kernel(PackArgs a, int32_t tile_bytes)
+{
+    __shared__ RunTable<kWideMaxRuns> tab;
+    const int tid = (int)threadIdx.x;
+    const int64_t F = a.frame_bytes;
+    const int64_t total_bytes = a.total_slots * F;
+    const int64_t D0 = (int64_t)blockIdx.x * tile_bytes;
+    const int64_t D1 = min(D0 + (int64_t)tile_bytes, total_bytes);
+    const int64_t gs_lo = D0 / F;                    // first slot touched
+    const int64_t gs_hi = (D1 + F - 1) / F;          // one past the last slot touched
+
+    if (wave_id() == 0) find_runs(a, gs_lo, gs_hi, tab);
+    __syncthreads();
+    const int n = tab.n;
+
+    // payload: runs in order, zeros in the gaps (block tails)
+    int64_t cursor = D0;
+    for (int r = 0; r < n; ++r) {
+        const int64_t run_lo = (gs_lo + tab.dst[r]) * F;
+        const int64_t run_hi = run_lo + (int64_t)tab.len[r] * F;
+        const int64_t lo = max(max(run_lo, D0), cursor);
+        const int64_t hi = min(run_hi, D1);
+        if (hi <= lo) continue;
+        if (lo > cursor) write_range<true>(a.packed, cursor, lo, nullptr);
+        write_range<false>(a.packed, lo, hi, a.src + tab.src[r] * F + (lo - run_lo));
+        cursor = hi;
+    }
+    if (cursor < D1) write_range<true>(a.packed, cursor, D1, nullptr);
+
+    // start table of the slots whose first byte lies in this tile
+    const int64_t m_lo = gs_lo + ((gs_lo * F < D0) ? 1 : 0);
+    const int64_t m_hi = min(gs_hi, a.total_slots);
+    for (int64_t g = m_lo + tid; g < m_hi; g += kThreads) {
+        const int32_t slot = (int32_t)(g - gs_lo);
+        const int r = run_of_slot(tab, n, slot);
+        int32_t sid = -1, fid = -1;
+        if (r >= 0) {
+            const int64_t t = (int64_t)slot - tab.dst[r];
+            if (t < tab.len[r]) { sid = tab.seq[r]; fid = (int32_t)t; }
+        }
+        a.seq_id[g] = sid;
+        a.frame_idx[g] = fid;
+        a.reset[g] = (uint8_t)(fid == 0);
+        a.valid[g] = (uint8_t)(fid >= 0);
+    }
+}
+
+// ----------------------------------------------------------------- narrow
+
+constexpr int kNarrowSlots = 1024;                  // slots per workgroup
+constexpr int kNarrowMaxRuns = kNarrowSlots + 2;
+
+// The run a lane is currently reading from, kept in registers and advanced
+// as the lane walks over consecutive slots.
+template <int MAXRUNS>
+struct RunCursor {
+    const RunTable<MAXRUNS>& tab;
+    int r;
+    int32_t dst, len, next, seq;
+    int64_t src;
+
+    __device__ __forceinline__ RunCursor(const RunTable<MAXRUNS>& t, int n, int32_t slot)
+        : tab(t)
+    {
+        r = run_of_slot(t, n, slot);
+        load();
+    }
+    __device__ __forceinline__ void load()
+    {
+        next = tab.dst[r + 1];
+        if (r >= 0) { dst = tab.dst[r]; len = tab.len[r]; seq = tab.seq[r]; src = tab.src[r]; }
+        else        { dst = 0; len = 0; seq = -1; src = 0; }
+    }
+    // frame index of `slot` inside the current run, or -1 on padding
+    __device__ __forceinline__ int32_t seek(int32_t slot)
+    {
+        while (slot >= next) { ++r; load(); }
+        const int64_t t = (int64_t)slot - dst;
+        return (r >= 0 && t < len) ? (int32_t)t : -1;
+    }
+};
+
+template <typename E>
+__global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a)
+{
+    __shared__ RunTable<kNarrowMaxRuns> tab;
+    const int tid = (int)threadIdx.x;
+    const int64_t g0 = (int64_t)blockIdx.x * kNarrowSlots;
+    const int64_t g1 = min(g0 + kNarrowSlots, a.total_slots);
+    const int nslot = (int)(g1 - g0);
+
+    if (wave_id() == 0) find_runs(a, g0, g1, tab);
+    __syncthreads();
+    const int n = tab.n;
+
+    // start table: 4 consecutive slots per lane -> 16-byte / 4-byte stores
+    for (int q = tid; 4 * q < nslot; q += kThreads) {
+        const int32_t s0 = 4 * q;
+        RunCursor<kNarrowMaxRuns> cur(tab, n, s0);
+        int32_t sid[4], fid[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            fid[j] = (s0 + j < nslot) ? cur.seek(s0 + j) : -1;
+            sid[j] = fid[j] >= 0 ? cur.seq : -1;
+        }
+        const int64_t g = g0 + s0;
+        if (s0 + 4 <= nslot) {
+            const vec16 vs = {(uint32_t)sid[0], (uint32_t)sid[1], (uint32_t)sid[2], (uint32_t)sid[3]};
+            const vec16 vf = {(uint32_t)fid[0], (uint32_t)fid[1], (uint32_t)fid[2], (uint32_t)fid[3]};
+            store_stream(reinterpret_cast<vec16*>(a.seq_id + g), vs);
+            store_stream(reinterpret_cast<vec16*>(a.frame_idx + g), vf);
+            uint32_t rs = 0, vl = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                rs |= (uint32_t)(fid[j] == 0) << (8 * j);
+                vl |= (uint32_t)(fid[j] >= 0) << (8 * j);
+            }
+            __builtin_nontemporal_store(rs, reinterpret_cast<uint32_t*>(a.reset + g));
+            __builtin_nontemporal_store(vl, reinterpret_cast<uint32_t*>(a.valid + g));
+        } else {
+            for (int j = 0; s0 + j < nslot; ++j) {
+                a.seq_id[g + j] = sid[j];
+                a.frame_idx[g + j] = fid[j];
+                a.reset[g + j] = (uint8_t)(fid[j] == 0);
+                a.valid[g + j] = (uint8_t)(fid[j] >= 0);
+            }
+        }
+    }
+
+    // payload: one 16-byte destination vector per lane and step, assembled
+    // from elements of type E (k elements per frame)
+    constexpr int EPV = 16 / (int)sizeof(E);
+    const int32_t k = (int32_t)(a.frame_bytes / (int64_t)sizeof(E));
+    const int32_t tile_elems = nslot * k;                       // < 1024 * 256
+    const int32_t nvec = (tile_elems + EPV - 1) / EPV;
+    const E* src = reinterpret_cast<const E*>(a.src);
+    uint8_t* dst_tile = a.packed + g0 * a.frame_bytes;          // 16-byte aligned
+    for (int32_t v = tid; v < nvec; v += kThreads) {
+        const int32_t w = v * EPV;
+        int32_t slot = w / k;
+        int32_t j = w - slot * k;
+        RunCursor<kNarrowMaxRuns> cur(tab, n, slot);
+        const int nvalid = min(EPV, tile_elems - w);
+        union { vec16 vec; E e[EPV]; } u;
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) {
+            E val{};
+            if (e < nvalid) {
+                const int32_t t = cur.seek(slot);
+                if (t >= 0) val = src[(cur.src + t) * k + j];
+                if (++j == k) { j = 0; ++slot; }
+            }
+            u.e[e] = val;
+        }
+        if (nvalid == EPV) {
+            store_stream(reinterpret_cast<vec16*>(dst_tile) + v, u.vec);
+        } else {
+            for (int e = 0; e < nvalid; ++e) reinterpret_cast<E*>(dst_tile)[w + e] = u.e[e];
+        }
+    }
+}
+
+}  // namespace bload
+
+using namespace bload;
+
+extern "C" bload_status bload_pack(const void* d_src, const int64_t* d_src_offsets,
+                                   const int32_t* d_lengths, const int32_t* d_order,
+                                   const int32_t* d_block_of_seq, const int32_t* d_offset_of_seq,
+                                   const int32_t* d_block_first, int64_t n_seq, int64_t num_blocks,
+                                   int32_t t_blk, int64_t frame_bytes, void* d_packed,
+                                   int32_t* d_seq_id, int32_t* d_frame_idx, uint8_t* d_reset,
+                                   uint8_t* d_valid, void* hip_stream)
+{
+    if (n_seq < 0 || num_blocks < 0 || t_blk < 1 || frame_bytes < 1) return BLOAD_EINVAL;
+    if (n_seq > BLOAD_MAX_SEQ || num_blocks > n_seq) return n_seq > BLOAD_MAX_SEQ ? BLOAD_EOVERFLOW
+                                                                                 : BLOAD_EINVAL;
+    if (n_seq == 0 || num_blocks == 0) return BLOAD_OK;
+    if (!d_src || !d_src_offsets || !d_lengths || !d_order || !d_block_of_seq ||
+        !d_offset_of_seq || !d_block_first || !d_packed || !d_seq_id || !d_frame_idx ||
+        !d_reset || !d_valid)
+        return BLOAD_EINVAL;
+    const int64_t total_slots = num_blocks * (int64_t)t_blk;
+    if (total_slots >= ((int64_t)1 << 40) || frame_bytes >= ((int64_t)1 << 31) ||
+        total_slots > INT64_MAX / frame_bytes / 2)
+        return BLOAD_EOVERFLOW;
+    if (!aligned_to(d_packed, 16) || !aligned_to(d_seq_id, 16) || !aligned_to(d_frame_idx, 16) ||
+        !aligned_to(d_reset, 16) || !aligned_to(d_valid, 16) || !aligned_to(d_src_offsets, 8) ||
+        !aligned_to(d_lengths, 4) || !aligned_to(d_order, 4) || !aligned_to(d_block_of_seq, 4) ||
+        !aligned_to(d_offset_of_seq, 4) || !aligned_to(d_block_first, 4))
+        return BLOAD_EALIGN;
+
+    PackArgs a;
+    a.src = static_cast<const uint8_t*>(d_src);
+    a.src_offsets = d_src_offsets;
+    a.lengths = d_lengths;
+    a.order = d_order;
+    a.block_of_seq = d_block_of_seq;
+    a.offset_of_seq = d_offset_of_seq;
+    a.block_first = d_block_first;
+    a.n_seq = (int32_t)n_seq;
+    a.t_blk = t_blk;
+    a.frame_bytes = frame_bytes;
+    a.total_slots = total_slots;
+    a.packed = static_cast<uint8_t*>(d_packed);
+    a.seq_id = d_seq_id;
+    a.frame_idx = d_frame_idx;
+    a.reset = d_reset;
+    a.valid = d_valid;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    if (frame_bytes >= kWideMinFrame) {
+        const int64_t total_bytes = total_slots * frame_bytes;
+        // 64 KiB tiles; smaller ones when the tensor is small, so that the
+        // launch still has a few thousand workgroups
+        int32_t tile_bytes = kWideTileMax;
+        while (tile_bytes > 4096 && total_bytes / tile_bytes < 4096) tile_bytes >>= 1;
+        const int64_t tiles = ceil_div(total_bytes, tile_bytes);
+        if (tiles > INT32_MAX) return BLOAD_EOVERFLOW;
+        hipLaunchKernelGGL(pack_wide_kernel, dim3((uint32_t)tiles), dim3(kThreads), 0, stream, a,
+                           tile_bytes);
+    } else {
+        const int64_t tiles = ceil_div(total_slots, kNarrowSlots);
+        if (tiles > INT32_MAX) return BLOAD_EOVERFLOW;
+        const dim3 grid((uint32_t)tiles), block(kThreads);
+        if (frame_bytes % 16 == 0 && aligned_to(d_src, 16))
+            hipLaunchKernelGGL(pack_narrow_kernel<vec16>, grid, block, 0, stream, a);
+        else if (frame_bytes % 4 == 0 && aligned_to(d_src, 4))
+            hipLaunchKernelGGL(pack_narrow_kernel<uint32_t>, grid, block, 0, stream, a);
+        else if (frame_bytes % 2 == 0 && aligned_to(d_src, 2))
+            hipLaunchKernelGGL(pack_narrow_kernel<uint16_t>, grid, block, 0, stream, a);
+        else
+            hipLaunchKernelGGL(pack_narrow_kernel<uint8_t>, grid, block, 0, stream, a);
+    }
+    return launch_status();
+}
