@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark of the BLoad block packer on one MI355X.
+
+A step is one pass of the whole path over one synthetic workload that is
+already resident in HBM: bload_plan (order + next-fit), bload_pack (gather,
+zero padding, start table) and bload_segment_reduce (per-sequence reduction
+over the packed blocks).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2] [--no-cpu-baseline]
+
+value      valid frames packed per second over the whole path (all K steps)
+roofline   the gather/pad kernel against the HBM roofline: algorithmic bytes
+           of one launch / its mean duration measured with events on the
+           stream it runs on
+cpu_baseline  the CPU oracle, one thread, timed on the same workload
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
+
+
+def measured_traffic(kernel_source: str, workload: int):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, or None
+    when there is none for this workload or the kernel source changed since."""
+    path = os.path.join(ROOT, "profiles", f"bload_pack_workload{workload}_hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        rec = json.load(f)
+    with open(kernel_source, "rb") as f:
+        digest = hashlib.sha256(f.read()).hexdigest()
+    if rec.get("kernel_source_sha256") != digest:
+        return None
+    return rec.get("hbm_bytes_per_launch")
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the packer runs on a single MI355X and this build has "
+              "no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2310_10879_amd import bload, workloads
+
+    w = workloads.WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    L = workloads.lengths(w.wid)
+    so = workloads.src_offsets(L)
+    total_frames = int(so[-1])
+    src = workloads.source(w.wid, 0, total_frames, threads=16)
+    d_src = torch.from_numpy(src.view(np.uint8).reshape(-1)).to(dev)
+    d_so = torch.from_numpy(so).to(dev)
+    d_L = torch.from_numpy(L).to(dev)
+    F, T, N, D = w.frame_bytes, w.t_blk, w.n_seq, w.frame_elems
+    seed = 0
+
+    # everything the steps write is allocated once, outside the timed region
+    plan_ws = torch.empty(max(16, bload.bload_plan_workspace_bytes(N)), dtype=torch.uint8, device=dev)
+    plan = bload.bload_plan(d_L, T, seed, workspace=plan_ws)
+    B = plan.num_blocks
+    packed = bload.alloc_packed(B, T, F, dev)
+    red_ws = torch.empty(max(16, bload.bload_segment_reduce_workspace_bytes(B, T, D, w.dtype)),
+                         dtype=torch.uint8, device=dev)
+    red = torch.zeros((N, D), dtype=torch.int64 if w.dtype == "i32" else torch.float32, device=dev)
+
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+
+    def step(events=None):
+        if events:
+            events[0].record()
+        bload.bload_plan(d_L, T, seed, workspace=plan_ws, out=plan)
+        if events:
+            events[1].record()
+        bload.bload_pack(d_src, d_so, d_L, plan, F, out=packed)
+        if events:
+            events[2].record()
+        bload.bload_segment_reduce(packed.packed, packed.seq_id, packed.reset, packed.valid,
+                                   plan.num_blocks, T, D, w.dtype, w.op, N, out=red,
+                                   workspace=red_ws)
+        if events:
+            events[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(ev[k])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert plan.num_blocks == B and plan.total_frames == total_frames
+
+    ms = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in ev])   # plan, pack, reduce
+    plan_ms, pack_ms, reduce_ms = (float(x) for x in ms.mean(axis=0))
+    ms_per_step = elapsed / args.steps * 1e3
+
+    slots = B * T
+    acc = 8 if w.dtype == "i32" else 4
+    bytes_pack = total_frames * F + slots * F + 10 * slots + 16 * N
+    bytes_reduce = slots * (F + 6) + N * D * acc
+    pack_gbps = bytes_pack / (pack_ms * 1e-3) / 1e9
+    pad_blocks = slots - total_frames
+    pad_longest = N * T - total_frames
+    kernel_src = os.path.join(ROOT, "paper_2310_10879_amd", "csrc", "bload_pack.hip")
+    traffic = measured_traffic(kernel_src, w.wid)
+
+    result = {
+        "metric": "packed_frames_per_s",
+        "value": total_frames * args.steps / elapsed,
+        "unit": "frames/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {
+            "workload": f"{w.wid}: N={N} {w.name}, T_blk={T}, frame_bytes={F}, seed={seed}",
+            "n_seq": N, "t_blk": T, "frame_bytes": F, "total_frames": total_frames,
+            "num_blocks": B, "lengths": "lognormal(mu=ln 60, sigma=1) clipped to [1,600]"
+            if w.wid == 2 else "see workloads.py",
+        },
+        "phases_ms": {"plan": plan_ms, "pack": pack_ms, "segment_reduce": reduce_ms},
+        "pack": {
+            "frames_per_s": total_frames / (pack_ms * 1e-3),
+            "algorithmic_GBps": pack_gbps,
+            "pct_of_hbm_peak": 100.0 * pack_gbps / HBM_PEAK_GBPS,
+            "min_ms": float(ms[:, 1].min()), "median_ms": float(np.median(ms[:, 1])),
+        },
+        "segment_reduce": {
+            "algorithmic_GBps": bytes_reduce / (reduce_ms * 1e-3) / 1e9,
+        },
+        "padding": {
+            "fill": total_frames / slots,
+            "pad_blocks_frames": pad_blocks,
+            "pad_to_longest_frames": pad_longest,
+            "pad_ratio_blocks": pad_blocks / slots,
+            "pad_ratio_to_longest": pad_longest / (N * T),
+            "reduction_vs_pad_to_longest": pad_longest / max(1, pad_blocks),
+        },
+        "roofline": {
+            "kernel": "pack_wide_kernel" if F >= 256 else "pack_narrow_kernel",
+            "bound": "hbm",
+            "achieved": pack_gbps,
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": pack_gbps / HBM_PEAK_GBPS,
+            "algorithmic_bytes_per_launch": bytes_pack,
+            "launch_ms": pack_ms,
+            "traffic": traffic,
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        # the oracle as it stands, one thread: order + plan + pack + reduce of the same workload
+        out = oracle.alloc_pack_outputs(B, T, F)
+        c0 = time.perf_counter()
+        ref_plan = oracle.plan(L, T, oracle.order(N, seed))
+        c1 = time.perf_counter()
+        oracle.pack(src, so, L, ref_plan, F, out=out)
+        c2 = time.perf_counter()
+        oracle.segment_reduce(src, so, L, D, w.dtype, w.op)
+        c3 = time.perf_counter()
+        assert ref_plan.num_blocks == B
+        result["cpu_baseline"] = {
+            "value": total_frames / (c3 - c0),
+            "unit": "frames/s",
+            "cores": 1,
+            "kind": "oracle",
+            "sample": f"the whole workload once ({N} sequences, {total_frames} frames): "
+                      f"plan {c1 - c0:.3f} s, pack {c2 - c1:.3f} s, reduce {c3 - c2:.3f} s",
+            "host_cores_visible": os.cpu_count(),
+        }
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

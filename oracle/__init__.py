@@ -127,10 +127,19 @@ def plan(lengths, t_blk: int, order_) -> Plan:
                 b, int(tot[0]), t_blk)
 
 
+def alloc_pack_outputs(nb: int, t_blk: int, frame_bytes: int):
+    """Output arrays for ``pack_blocks``, prefilled with garbage so that a slot the
+    oracle fails to write shows up."""
+    return (np.full((nb, t_blk, frame_bytes), 0xA5, dtype=np.uint8),
+            np.full((nb, t_blk), -9, dtype=np.int32), np.full((nb, t_blk), -9, dtype=np.int32),
+            np.full((nb, t_blk), 9, dtype=np.uint8), np.full((nb, t_blk), 9, dtype=np.uint8))
+
+
 def pack_blocks(src, src_offsets, lengths, pl: Plan, frame_bytes: int, block_lo: int,
-                block_hi: int):
+                block_hi: int, out=None):
     """Blocks [block_lo, block_hi) -> (packed u8[nb, T, frame_bytes], seq_id i32[nb, T],
-    frame_idx i32[nb, T], reset u8[nb, T], valid u8[nb, T])."""
+    frame_idx i32[nb, T], reset u8[nb, T], valid u8[nb, T]); ``out`` may bring
+    preallocated arrays of those shapes."""
     src = np.ascontiguousarray(src)
     src_b = src.view(np.uint8).reshape(-1)
     so = _c(src_offsets, np.int64)
@@ -139,11 +148,9 @@ def pack_blocks(src, src_offsets, lengths, pl: Plan, frame_bytes: int, block_lo:
     assert src_b.shape[0] == int(so[-1]) * frame_bytes if n else True
     nb = block_hi - block_lo
     T = pl.t_blk
-    packed = np.full((nb, T, frame_bytes), 0xA5, dtype=np.uint8)
-    seq_id = np.full((nb, T), -9, dtype=np.int32)
-    frame_idx = np.full((nb, T), -9, dtype=np.int32)
-    reset = np.full((nb, T), 9, dtype=np.uint8)
-    valid = np.full((nb, T), 9, dtype=np.uint8)
+    packed, seq_id, frame_idx, reset, valid = (alloc_pack_outputs(nb, T, frame_bytes)
+                                               if out is None else out)
+    assert packed.shape == (nb, T, frame_bytes) and packed.dtype == np.uint8
     _load().bload_oracle_pack_blocks(_p(src_b), _p(so), _p(L), _p(pl.block_of_seq),
                                      _p(pl.offset_of_seq), n, T, frame_bytes, block_lo,
                                      block_hi, _p(packed), _p(seq_id), _p(frame_idx),
@@ -151,8 +158,8 @@ def pack_blocks(src, src_offsets, lengths, pl: Plan, frame_bytes: int, block_lo:
     return packed, seq_id, frame_idx, reset, valid
 
 
-def pack(src, src_offsets, lengths, pl: Plan, frame_bytes: int):
-    return pack_blocks(src, src_offsets, lengths, pl, frame_bytes, 0, pl.num_blocks)
+def pack(src, src_offsets, lengths, pl: Plan, frame_bytes: int, out=None):
+    return pack_blocks(src, src_offsets, lengths, pl, frame_bytes, 0, pl.num_blocks, out)
 
 
 def segment_reduce(src, src_offsets, lengths, feat_dim: int, dtype: str, op: str) -> np.ndarray:

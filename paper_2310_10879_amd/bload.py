@@ -45,11 +45,10 @@ _lib.bload_plan.argtypes = [_vp, _i64, _i32, _u64, _vp, _vp, _vp, _vp,
 _lib.bload_pack.restype = ctypes.c_int
 _lib.bload_pack.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i32, _i64,
                             _vp, _vp, _vp, _vp, _vp, _vp]
-if hasattr(_lib, "bload_segment_reduce"):
-  _lib.bload_segment_reduce_workspace_bytes.restype = _sz
-  _lib.bload_segment_reduce_workspace_bytes.argtypes = [_i64, _i32, _i64, ctypes.c_int]
-  _lib.bload_segment_reduce.restype = ctypes.c_int
-  _lib.bload_segment_reduce.argtypes = [_vp, _vp, _vp, _vp, _i64, _i32, _i64, ctypes.c_int,
+_lib.bload_segment_reduce_workspace_bytes.restype = _sz
+_lib.bload_segment_reduce_workspace_bytes.argtypes = [_i64, _i32, _i64, ctypes.c_int]
+_lib.bload_segment_reduce.restype = ctypes.c_int
+_lib.bload_segment_reduce.argtypes = [_vp, _vp, _vp, _vp, _i64, _i32, _i64, ctypes.c_int,
                                       ctypes.c_int, _i64, _vp, _vp, _sz, _vp]
 
 

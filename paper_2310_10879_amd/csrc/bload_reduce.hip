@@ -1,0 +1,614 @@
+// bload_segment_reduce: per-sequence sum / mean over the packed blocks, using
+// only the packed tensor and the per-slot start table (BLoad, Methods section:
+// the table of starting indices lets a consumer that carries state from frame
+// to frame drop it where a new sequence begins).
+//
+// A segment is a maximal run of valid slots inside one block that begins at a
+// reset flag (or at the block's first slot) and contains no other reset flag.
+// Time is cut into chunks; every chunk reduces the pieces of segments that lie
+// in it.  A piece that is a whole segment goes straight to the output.  A
+// piece cut by a chunk border goes to a partial buffer: "head" partial = the
+// piece that continues a segment begun in an earlier chunk, "tail" partial =
+// the piece that begins a segment continued in the next chunk.  A second
+// small kernel adds tail + following heads in time order.  Fixed chunking and
+// fixed order make the float32 result bit-reproducible.
+//
+// Two layouts of the work:
+//   wide   (a frame is >= 64 bytes): lanes across the features of a frame, each
+//          row of lanes walks one chunk of time serially with several loads in
+//          flight, restarting its accumulators at every start flag.
+//   narrow (small frames, e.g. one token): lanes across time, 16 consecutive
+//          slots per lane, segmented scan over the workgroup with the start
+//          flags as segment heads and a carry between lanes and waves.
+#include "bload_common.hpp"
+
+#include <hip/hip_fp16.h>
+#include <limits.h>
+
+namespace bload {
+
+constexpr int kHeadNone = 0, kHeadClosed = 1, kHeadThrough = 2;
+
+struct ChunkDesc {
+    int32_t head_state;   // kHead*: is there a piece continuing an earlier segment, and does
+                          // it run through the whole chunk into the next one
+    int32_t cnt_head;     // frames in that piece
+    int32_t cnt_tail;     // frames in the piece that continues into the next chunk, 0 if none
+    int32_t seq_tail;     // sequence id of that piece
+};
+
+struct ReduceArgs {
+    const uint8_t* packed;
+    const int32_t* seq_id;
+    const uint8_t* reset;
+    const uint8_t* valid;
+    int64_t num_blocks;
+    int64_t total_slots;
+    int64_t total_chunks;
+    int32_t t_blk;
+    int32_t feat_dim;
+    int32_t n_seq;
+    int32_t mean;            // 1: divide by the frame count
+    void* out;               // [n_seq, feat_dim] float or int64
+    // chunking
+    int32_t chunk;           // slots per chunk
+    int32_t n_chunks;        // wide: chunks per block
+    int32_t row_lanes_log2;  // wide: lanes per row = 1 << this
+    int32_t n_vec;           // wide: lanes needed to cover one frame
+    // partial buffers (null when no chunk border can cut a segment)
+    ChunkDesc* desc;         // [total_chunks]
+    void* head_part;         // [total_chunks, feat_dim] accumulators
+    void* tail_part;         // [total_chunks, feat_dim]
+};
+
+// ---- element access -----------------------------------------------------------
+
+template <typename ElemT> struct Elem;
+template <> struct Elem<uint8_t> {
+    typedef float Acc;
+    __device__ static float get(uint8_t v) { return (float)v; }
+};
+struct half_bits { uint16_t bits; };           // IEEE binary16 storage
+template <> struct Elem<half_bits> {
+    typedef float Acc;
+    __device__ static float get(half_bits v) { return __half2float(__ushort_as_half(v.bits)); }
+};
+template <> struct Elem<float> {
+    typedef float Acc;
+    __device__ static float get(float v) { return v; }
+};
+template <> struct Elem<int32_t> {
+    typedef long long Acc;
+    __device__ static long long get(int32_t v) { return (long long)v; }
+};
+
+// VEC elements of one lane: a 16-byte vector (VEC = 16 / sizeof(ElemT)) or one element.
+template <typename ElemT, int VEC>
+struct LaneData {
+    union { vec16 v; ElemT e[VEC > 1 ? VEC : 1]; } u;
+    __device__ __forceinline__ void load(const uint8_t* p)
+    {
+        if (VEC > 1) u.v = load_stream(reinterpret_cast<const vec16*>(p));
+        else u.e[0] = *reinterpret_cast<const ElemT*>(p);
+    }
+};
+
+template <typename Acc> struct OutOf;
+template <> struct OutOf<float> { typedef float T; };
+template <> struct OutOf<long long> { typedef long long T; };
+
+template <typename Acc>
+__device__ __forceinline__ Acc finish(Acc sum, int32_t cnt, int mean)
+{
+    return sum;
+}
+template <>
+__device__ __forceinline__ float finish<float>(float sum, int32_t cnt, int mean)
+{
+    return mean ? sum / (float)cnt : sum;
+}
+
+// ------------------------------------------------------------------- wide
+
+constexpr int kWideUnroll = 4;
+constexpr int kWideFlagBytes = 32768;      // LDS budget for the staged flags
+
+template <typename ElemT, int VEC>
+__global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
+{
+    typedef typename Elem<ElemT>::Acc Acc;
+    extern __shared__ uint8_t s_flags[];   // rows x (chunk + 1): bit0 valid, bit1 reset
+    const int tid = (int)threadIdx.x;
+    const int C = a.chunk, stride = C + 1;
+    const int rows = kThreads >> a.row_lanes_log2;
+    const int64_t q_base = (int64_t)blockIdx.x * rows;
+    const int64_t T = a.t_blk;
+
+    // stage the flags of this workgroup's chunks, plus the slot after each chunk
+    for (int r = 0; r < rows; ++r) {
+        const int64_t q = q_base + r;
+        if (q >= a.total_chunks) break;
+        const int64_t b = q / a.n_chunks;
+        const int32_t t0 = (int32_t)(q - b * a.n_chunks) * C;
+        const int32_t len = min(C, a.t_blk - t0);
+        const int64_t g = b * T + t0;
+        for (int t = tid; t <= len; t += kThreads) {
+            uint8_t f = 0;
+            if (t0 + t < a.t_blk) f = (uint8_t)((a.valid[g + t] ? 1 : 0) | (a.reset[g + t] ? 2 : 0));
+            s_flags[r * stride + t] = f;
+        }
+    }
+    __syncthreads();
+
+    const int row = tid >> a.row_lanes_log2;
+    const int col = tid & ((1 << a.row_lanes_log2) - 1);
+    const int64_t q = q_base + row;
+    const int fv = (int)blockIdx.y * (1 << a.row_lanes_log2) + col;    // which lane-slice of the frame
+    if (q >= a.total_chunks || fv >= a.n_vec) return;
+
+    const int64_t b = q / a.n_chunks;
+    const int32_t t0 = (int32_t)(q - b * a.n_chunks) * C;
+    const int32_t len = min(C, a.t_blk - t0);
+    const int64_t g = b * T + t0;
+    const uint8_t* flags = s_flags + row * stride;
+    const int64_t frame_bytes = (int64_t)a.feat_dim * (int64_t)sizeof(ElemT);
+    const uint8_t* lane_src = a.packed + g * frame_bytes + (int64_t)fv * VEC * (int64_t)sizeof(ElemT);
+    const int64_t feat0 = (int64_t)fv * VEC;
+    const bool writes_desc = (col == 0 && blockIdx.y == 0 && a.desc != nullptr);
+    typedef typename OutOf<Acc>::T Out;
+    Out* out = static_cast<Out*>(a.out);
+    Acc* head_part = static_cast<Acc*>(a.head_part);
+    Acc* tail_part = static_cast<Acc*>(a.tail_part);
+
+    Acc acc[VEC];
+    bool open = false, head_open = false;
+    int32_t cnt = 0, last = 0;
+    ChunkDesc desc{kHeadNone, 0, 0, -1};
+
+    // close the piece that is being accumulated; `closed` = the segment ends here
+    auto flush = [&](bool closed) {
+        if (head_open) {
+            if (head_part) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) head_part[q * a.feat_dim + feat0 + e] = acc[e];
+            }
+            desc.head_state = closed ? kHeadClosed : kHeadThrough;
+            desc.cnt_head = cnt;
+        } else {
+            const int32_t seq = a.seq_id[g + last];
+            if (closed) {
+                if ((uint32_t)seq < (uint32_t)a.n_seq) {
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e)
+                        out[(int64_t)seq * a.feat_dim + feat0 + e] = finish<Acc>(acc[e], cnt, a.mean);
+                }
+            } else {
+                if (tail_part) {
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) tail_part[q * a.feat_dim + feat0 + e] = acc[e];
+                }
+                desc.cnt_tail = cnt;
+                desc.seq_tail = seq;
+            }
+        }
+    };
+
+    for (int32_t t = 0; t < len; t += kWideUnroll) {
+        LaneData<ElemT, VEC> x[kWideUnroll];
+        uint8_t f[kWideUnroll];
+#pragma unroll
+        for (int u = 0; u < kWideUnroll; ++u) {
+            f[u] = (t + u < len) ? flags[t + u] : (uint8_t)0;
+            if (f[u] & 1) x[u].load(lane_src + (int64_t)(t + u) * frame_bytes);
+        }
+#pragma unroll
+        for (int u = 0; u < kWideUnroll; ++u) {
+            if (t + u >= len) break;
+            if (!(f[u] & 1)) {                     // padding ends whatever was open
+                if (open) { flush(true); open = false; }
+                continue;
+            }
+            const bool starts = (f[u] & 2) || (t0 + t + u == 0);
+            if (starts || !open) {
+                if (open) flush(true);
+                // a valid slot without a start flag continues the previous chunk's segment
+                head_open = !starts && (t + u == 0);
+                open = true;
+                cnt = 0;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[e] = 0;
+            }
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] += Elem<ElemT>::get(x[u].u.e[e]);
+            cnt += 1;
+            last = t + u;
+        }
+    }
+    if (open) {
+        const uint8_t nf = flags[len];             // the slot after the chunk (0 past the block)
+        flush(!(nf & 1) || (nf & 2));
+    }
+    if (writes_desc) a.desc[q] = desc;
+}
+
+// ----------------------------------------------------------------- narrow
+
+constexpr int kSlotsPerLane = 16;
+constexpr int kNarrowTile = kThreads * kSlotsPerLane;      // 4096 slots per workgroup
+
+// Running state of a segmented sum: `any` = a segment break was seen.
+template <typename Acc>
+struct SegState { Acc sum; int32_t cnt; int32_t any; };
+
+template <typename Acc>
+__device__ __forceinline__ SegState<Acc> seg_combine(SegState<Acc> left, SegState<Acc> right)
+{
+    SegState<Acc> r;
+    r.sum = right.any ? right.sum : left.sum + right.sum;
+    r.cnt = right.any ? right.cnt : left.cnt + right.cnt;
+    r.any = left.any | right.any;
+    return r;
+}
+
+__device__ __forceinline__ float shfl_up_acc(float v, int d) { return __shfl_up(v, d, kWave); }
+__device__ __forceinline__ long long shfl_up_acc(long long v, int d) { return __shfl_up(v, d, kWave); }
+
+template <typename Acc>
+__device__ __forceinline__ SegState<Acc> seg_shfl_up(SegState<Acc> s, int d)
+{
+    SegState<Acc> r;
+    r.sum = shfl_up_acc(s.sum, d);
+    r.cnt = __shfl_up(s.cnt, d, kWave);
+    r.any = __shfl_up(s.any, d, kWave);
+    return r;
+}
+
+template <typename ElemT>
+__global__ __launch_bounds__(kThreads) void reduce_narrow_kernel(ReduceArgs a)
+{
+    typedef typename Elem<ElemT>::Acc Acc;
+    typedef typename OutOf<Acc>::T Out;
+    __shared__ SegState<Acc> s_wave[kThreads / kWave];
+    __shared__ uint32_t s_first_brk[kThreads / kWave];
+    __shared__ ChunkDesc s_desc;
+
+    const int tid = (int)threadIdx.x;
+    const int lane = lane_id(), wave = wave_id();
+    const int64_t S = a.total_slots;
+    const int64_t T = a.t_blk;
+    const int64_t q = blockIdx.x;
+    const int64_t g0 = q * kNarrowTile;
+    const int64_t g1 = min(S, g0 + kNarrowTile);
+    const int64_t s0 = g0 + (int64_t)tid * kSlotsPerLane;
+    const int D = a.feat_dim;
+    Out* out = static_cast<Out*>(a.out);
+    Acc* head_part = static_cast<Acc*>(a.head_part);
+    Acc* tail_part = static_cast<Acc*>(a.tail_part);
+
+    // flags of this lane's 16 slots: bit j of vmask = valid, of bmask = segment break
+    // (a break is a padding slot, a start flag, or the first slot of a block)
+    uint32_t vmask = 0, bmask = 0;
+    {
+        uint8_t rs[kSlotsPerLane], vl[kSlotsPerLane];
+        if (s0 + kSlotsPerLane <= S) {
+            union { vec16 v; uint8_t b[16]; } ur, uv;
+            ur.v = load_stream(reinterpret_cast<const vec16*>(a.reset + s0));
+            uv.v = load_stream(reinterpret_cast<const vec16*>(a.valid + s0));
+#pragma unroll
+            for (int j = 0; j < kSlotsPerLane; ++j) { rs[j] = ur.b[j]; vl[j] = uv.b[j]; }
+        } else {
+#pragma unroll
+            for (int j = 0; j < kSlotsPerLane; ++j) {
+                const bool in = s0 + j < S;
+                rs[j] = in ? a.reset[s0 + j] : (uint8_t)0;
+                vl[j] = in ? a.valid[s0 + j] : (uint8_t)0;
+            }
+        }
+        int64_t rem = s0 % T;                       // slot inside its block
+#pragma unroll
+        for (int j = 0; j < kSlotsPerLane; ++j) {
+            const bool v = vl[j] != 0;
+            const bool brk = !v || rs[j] != 0 || rem == 0;
+            vmask |= (uint32_t)v << j;
+            bmask |= (uint32_t)brk << j;
+            if (++rem == T) rem = 0;
+        }
+    }
+    // does a segment end at slot j: it is valid and the next slot is a break
+    if (lane == 0) s_first_brk[wave] = bmask & 1u;
+    if (tid == 0) s_desc = ChunkDesc{kHeadNone, 0, 0, -1};
+    __syncthreads();
+    uint32_t next_first = __shfl_down(bmask & 1u, 1, kWave);
+    if (lane == kWave - 1) {
+        if (wave + 1 < kThreads / kWave) {
+            next_first = s_first_brk[wave + 1];
+        } else {
+            // the slot after the tile: past the end or a block's first slot closes the segment
+            next_first = 1u;
+            if (g0 + kNarrowTile < S && (g0 + kNarrowTile) % T != 0)
+                next_first = (!a.valid[g0 + kNarrowTile] || a.reset[g0 + kNarrowTile]) ? 1u : 0u;
+        }
+    }
+    const uint32_t next_brk = (bmask >> 1) | (next_first << (kSlotsPerLane - 1));
+    const uint32_t ends = vmask & next_brk;
+    // the tile's last slot, if its segment goes on into the next tile
+    const bool owns_last = (g1 - 1 >= s0) && (g1 - 1 < s0 + kSlotsPerLane);
+    const int j_last = (int)(g1 - 1 - s0);
+    const bool tail_open = owns_last && ((vmask >> j_last) & 1u) && !((next_brk >> j_last) & 1u);
+
+    const int64_t esize = (int64_t)sizeof(ElemT);
+    const bool vec_payload = (D == 1) && (sizeof(ElemT) == 4) && (s0 + kSlotsPerLane <= S);
+
+    for (int d = 0; d < D; ++d) {
+        // this lane's elements of feature d
+        Acc x[kSlotsPerLane];
+        if (vec_payload) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                union { vec16 v; ElemT e[4]; } u;
+                u.v = load_stream(reinterpret_cast<const vec16*>(a.packed + (s0 + 4 * k) * esize));
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    x[4 * k + j] = ((vmask >> (4 * k + j)) & 1u) ? Elem<ElemT>::get(u.e[j]) : (Acc)0;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < kSlotsPerLane; ++j) {
+                x[j] = 0;
+                if ((vmask >> j) & 1u)
+                    x[j] = Elem<ElemT>::get(*reinterpret_cast<const ElemT*>(
+                        a.packed + ((s0 + j) * D + d) * esize));
+            }
+        }
+        // segmented running sums inside the lane
+        SegState<Acc> run{0, 0, 0};
+        Acc incl[kSlotsPerLane];
+        int32_t cincl[kSlotsPerLane];
+#pragma unroll
+        for (int j = 0; j < kSlotsPerLane; ++j) {
+            if ((bmask >> j) & 1u) { run.sum = 0; run.cnt = 0; run.any = 1; }
+            run.sum += x[j];
+            run.cnt += (int32_t)((vmask >> j) & 1u);
+            incl[j] = run.sum;
+            cincl[j] = run.cnt;
+        }
+        // carry from the lanes before this one: wave scan, then the waves before this one
+        SegState<Acc> scan = run;
+#pragma unroll
+        for (int dd = 1; dd < kWave; dd <<= 1) {
+            const SegState<Acc> left = seg_shfl_up(scan, dd);
+            if (lane >= dd) scan = seg_combine(left, scan);
+        }
+        SegState<Acc> carry = seg_shfl_up(scan, 1);
+        if (lane == 0) carry = SegState<Acc>{0, 0, 0};
+        __syncthreads();                            // s_wave from the previous feature is consumed
+        if (lane == kWave - 1) s_wave[wave] = scan;
+        __syncthreads();
+        SegState<Acc> before{0, 0, 0};
+        for (int w = 0; w < wave; ++w) before = seg_combine(before, s_wave[w]);
+        carry = seg_combine(before, carry);
+
+        // emit the segments that end in this lane
+        const uint32_t first_brk_bit = bmask ? (uint32_t)(__ffs((int)bmask) - 1) : 32u;
+#pragma unroll
+        for (int j = 0; j < kSlotsPerLane; ++j) {
+            const bool is_end = (ends >> j) & 1u;
+            const bool is_tail = tail_open && j == j_last;
+            if (!is_end && !is_tail) continue;
+            const bool lane_started = (uint32_t)j >= first_brk_bit;     // a break at or before j in this lane
+            const Acc sum = lane_started ? incl[j] : carry.sum + incl[j];
+            const int32_t cnt = lane_started ? cincl[j] : carry.cnt + cincl[j];
+            const bool started = lane_started || carry.any;             // the segment began inside the tile
+            if (is_end && started) {
+                const int32_t seq = a.seq_id[s0 + j];
+                if ((uint32_t)seq < (uint32_t)a.n_seq)
+                    out[(int64_t)seq * D + d] = finish<Acc>(sum, cnt, a.mean);
+            } else if (!started) {
+                // continues a segment of the previous tile; closed here or running through
+                if (head_part) head_part[q * D + d] = sum;
+                if (d == 0) {
+                    s_desc.head_state = is_end ? kHeadClosed : kHeadThrough;
+                    s_desc.cnt_head = cnt;
+                }
+            } else {
+                if (tail_part) tail_part[q * D + d] = sum;
+                if (d == 0) {
+                    s_desc.cnt_tail = cnt;
+                    s_desc.seq_tail = a.seq_id[s0 + j];
+                }
+            }
+        }
+    }
+    __syncthreads();
+    if (tid == 0 && a.desc) a.desc[q] = s_desc;
+}
+
+// ----------------------------------------------------------------- stitch
+
+// Segments cut by chunk borders: tail piece + the head pieces of the following
+// chunks, added in time order.  One workgroup per (chunk, 256 features).
+template <typename Acc>
+__global__ __launch_bounds__(kThreads) void reduce_stitch_kernel(ReduceArgs a, int32_t feat_tiles)
+{
+    typedef typename OutOf<Acc>::T Out;
+    const int64_t q = (int64_t)blockIdx.x / feat_tiles;
+    const int64_t d = ((int64_t)blockIdx.x % feat_tiles) * kThreads + threadIdx.x;
+    const ChunkDesc first = a.desc[q];
+    if (first.cnt_tail <= 0 || d >= a.feat_dim) return;
+    const Acc* head_part = static_cast<const Acc*>(a.head_part);
+    const Acc* tail_part = static_cast<const Acc*>(a.tail_part);
+    Acc sum = tail_part[q * a.feat_dim + d];
+    int64_t cnt = first.cnt_tail;
+    for (int64_t q2 = q + 1; q2 < a.total_chunks; ++q2) {
+        const ChunkDesc nd = a.desc[q2];
+        if (nd.head_state == kHeadNone) break;
+        sum += head_part[q2 * a.feat_dim + d];
+        cnt += nd.cnt_head;
+        if (nd.head_state != kHeadThrough) break;
+    }
+    if ((uint32_t)first.seq_tail < (uint32_t)a.n_seq)
+        static_cast<Out*>(a.out)[(int64_t)first.seq_tail * a.feat_dim + d] =
+            finish<Acc>(sum, (int32_t)cnt, a.mean);
+}
+
+// ------------------------------------------------------------------- host
+
+struct ReducePlan {
+    bool wide;
+    int vec;                 // wide: elements per lane (16 / elem size, or 1)
+    int row_lanes_log2;
+    int n_vec;
+    int32_t chunk, n_chunks;
+    int64_t total_chunks;
+    bool partials;           // can a chunk border cut a segment
+    size_t desc_off, head_off, tail_off, bytes;
+};
+
+static int elem_size(bload_dtype dtype) { return dtype == BLOAD_U8 ? 1 : dtype == BLOAD_F16 ? 2 : 4; }
+
+static ReducePlan reduce_plan(int64_t num_blocks, int32_t t_blk, int64_t feat_dim, bload_dtype dtype)
+{
+    ReducePlan p{};
+    const int es = elem_size(dtype);
+    const int64_t frame_bytes = feat_dim * es;
+    const size_t acc = dtype == BLOAD_I32 ? 8 : 4;
+    const bool vectors = frame_bytes % 16 == 0 && frame_bytes >= 64;
+    p.wide = vectors || feat_dim >= 64;
+    if (p.wide) {
+        p.vec = vectors ? 16 / es : 1;
+        p.n_vec = (int)ceil_div(feat_dim, p.vec);
+        p.row_lanes_log2 = 0;
+        while ((1 << p.row_lanes_log2) < p.n_vec && p.row_lanes_log2 < 8) ++p.row_lanes_log2;
+        const int rows = kThreads >> p.row_lanes_log2;
+        const int64_t feat_tiles = ceil_div(p.n_vec, 1 << p.row_lanes_log2);
+        // enough chunks per block for ~2048 workgroups, each at least 64 slots long
+        int64_t want = ceil_div((int64_t)2048 * rows, num_blocks * feat_tiles);
+        const int64_t most = t_blk / 64 > 0 ? t_blk / 64 : 1;
+        if (want > most) want = most;
+        if (want < 1) want = 1;
+        int64_t chunk = ceil_div(t_blk, want);
+        const int64_t lds_cap = kWideFlagBytes / rows - 1;
+        if (chunk > lds_cap) chunk = lds_cap;
+        p.chunk = (int32_t)chunk;
+        p.n_chunks = (int32_t)ceil_div(t_blk, chunk);
+        p.total_chunks = num_blocks * p.n_chunks;
+        p.partials = p.n_chunks > 1;
+    } else {
+        p.chunk = kNarrowTile;
+        p.n_chunks = 0;
+        p.total_chunks = ceil_div(num_blocks * (int64_t)t_blk, kNarrowTile);
+        // tiles that always end on a block border never cut a segment
+        p.partials = (kNarrowTile % t_blk) != 0;
+    }
+    if (p.partials) {
+        size_t off = 0;
+        p.desc_off = off; off += round_up((size_t)p.total_chunks * sizeof(ChunkDesc), 16);
+        p.head_off = off; off += round_up((size_t)p.total_chunks * (size_t)feat_dim * acc, 16);
+        p.tail_off = off; off += round_up((size_t)p.total_chunks * (size_t)feat_dim * acc, 16);
+        p.bytes = off;
+    }
+    return p;
+}
+
+template <typename ElemT>
+static void launch_wide(const ReducePlan& p, const ReduceArgs& a, hipStream_t stream)
+{
+    const int rows = kThreads >> p.row_lanes_log2;
+    const dim3 grid((uint32_t)ceil_div(p.total_chunks, rows),
+                    (uint32_t)ceil_div(p.n_vec, 1 << p.row_lanes_log2));
+    const size_t lds = (size_t)rows * (size_t)(p.chunk + 1);
+    if (p.vec > 1)
+        hipLaunchKernelGGL((reduce_wide_kernel<ElemT, 16 / (int)sizeof(ElemT)>), grid, dim3(kThreads),
+                           lds, stream, a);
+    else
+        hipLaunchKernelGGL((reduce_wide_kernel<ElemT, 1>), grid, dim3(kThreads), lds, stream, a);
+}
+
+template <typename ElemT>
+static void launch_reduce(const ReducePlan& p, const ReduceArgs& a, hipStream_t stream)
+{
+    typedef typename Elem<ElemT>::Acc Acc;
+    if (p.wide) {
+        launch_wide<ElemT>(p, a, stream);
+    } else {
+        hipLaunchKernelGGL(reduce_narrow_kernel<ElemT>, dim3((uint32_t)p.total_chunks), dim3(kThreads),
+                           0, stream, a);
+    }
+    if (p.partials) {
+        const int32_t feat_tiles = (int32_t)ceil_div(a.feat_dim, kThreads);
+        hipLaunchKernelGGL(reduce_stitch_kernel<Acc>, dim3((uint32_t)(p.total_chunks * feat_tiles)),
+                           dim3(kThreads), 0, stream, a, feat_tiles);
+    }
+}
+
+}  // namespace bload
+
+using namespace bload;
+
+extern "C" size_t bload_segment_reduce_workspace_bytes(int64_t num_blocks, int32_t t_blk,
+                                                       int64_t feat_dim, bload_dtype dtype)
+{
+    if (num_blocks <= 0 || t_blk < 1 || feat_dim < 1 || (int)dtype < 0 || (int)dtype > 3) return 0;
+    return reduce_plan(num_blocks, t_blk, feat_dim, dtype).bytes;
+}
+
+extern "C" bload_status bload_segment_reduce(const void* d_packed, const int32_t* d_seq_id,
+                                             const uint8_t* d_reset, const uint8_t* d_valid,
+                                             int64_t num_blocks, int32_t t_blk, int64_t feat_dim,
+                                             bload_dtype dtype, bload_op op, int64_t n_seq,
+                                             void* d_out, void* d_workspace, size_t workspace_bytes,
+                                             void* hip_stream)
+{
+    if (num_blocks < 0 || t_blk < 1 || feat_dim < 1 || n_seq < 0) return BLOAD_EINVAL;
+    if ((int)dtype < 0 || (int)dtype > 3 || (int)op < 0 || (int)op > 1) return BLOAD_EINVAL;
+    if (dtype == BLOAD_I32 && op == BLOAD_MEAN) return BLOAD_EINVAL;
+    if (n_seq > BLOAD_MAX_SEQ || feat_dim >= ((int64_t)1 << 28)) return BLOAD_EOVERFLOW;
+    if (num_blocks == 0 || n_seq == 0) return BLOAD_OK;
+    if (!d_packed || !d_seq_id || !d_reset || !d_valid || !d_out) return BLOAD_EINVAL;
+    const int64_t total_slots = num_blocks * (int64_t)t_blk;
+    if (total_slots >= ((int64_t)1 << 40)) return BLOAD_EOVERFLOW;
+    if (!aligned_to(d_packed, 16) || !aligned_to(d_seq_id, 4) || !aligned_to(d_reset, 16) ||
+        !aligned_to(d_valid, 16) || !aligned_to(d_out, 8))
+        return BLOAD_EALIGN;
+
+    const ReducePlan p = reduce_plan(num_blocks, t_blk, feat_dim, dtype);
+    if (p.total_chunks * ceil_div(feat_dim, kThreads) > INT32_MAX) return BLOAD_EOVERFLOW;
+    if (p.wide && ceil_div(p.n_vec, 1 << p.row_lanes_log2) > 65535) return BLOAD_EOVERFLOW;
+    if (p.partials) {
+        if (!d_workspace) return BLOAD_EINVAL;
+        if (!aligned_to(d_workspace, 16)) return BLOAD_EALIGN;
+        if (workspace_bytes < p.bytes) return BLOAD_EWORKSPACE;
+    }
+
+    ReduceArgs a{};
+    a.packed = static_cast<const uint8_t*>(d_packed);
+    a.seq_id = d_seq_id;
+    a.reset = d_reset;
+    a.valid = d_valid;
+    a.num_blocks = num_blocks;
+    a.total_slots = total_slots;
+    a.total_chunks = p.total_chunks;
+    a.t_blk = t_blk;
+    a.feat_dim = (int32_t)feat_dim;
+    a.n_seq = (int32_t)n_seq;
+    a.mean = op == BLOAD_MEAN ? 1 : 0;
+    a.out = d_out;
+    a.chunk = p.chunk;
+    a.n_chunks = p.n_chunks;
+    a.row_lanes_log2 = p.row_lanes_log2;
+    a.n_vec = p.n_vec;
+    if (p.partials) {
+        uint8_t* ws = static_cast<uint8_t*>(d_workspace);
+        a.desc = reinterpret_cast<ChunkDesc*>(ws + p.desc_off);
+        a.head_part = ws + p.head_off;
+        a.tail_part = ws + p.tail_off;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    switch (dtype) {
+        case BLOAD_U8: launch_reduce<uint8_t>(p, a, stream); break;
+        case BLOAD_F16: launch_reduce<half_bits>(p, a, stream); break;
+        case BLOAD_F32: launch_reduce<float>(p, a, stream); break;
+        case BLOAD_I32: launch_reduce<int32_t>(p, a, stream); break;
+    }
+    return launch_status();
+}

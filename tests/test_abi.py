@@ -1,0 +1,101 @@
+"""The C-ABI library loads and exports every entry point that include/bload.h
+declares (no compute calls: this runs without a GPU), and the host-side
+argument checks answer before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "bload.h")
+LIB = os.path.join(ROOT, "paper_2310_10879_amd", "libbload.so")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bload_[a-z_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2310_10879_amd import build
+        build.build(verbose=False)
+    return ctypes.CDLL(LIB)
+
+
+def test_header_declares_the_three_entry_points():
+    names = declared_functions()
+    for must in ("bload_plan", "bload_pack", "bload_segment_reduce", "bload_plan_workspace_bytes",
+                 "bload_segment_reduce_workspace_bytes", "bload_status_string"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), f"{name} is declared in bload.h but not exported"
+
+
+def test_status_strings(lib):
+    lib.bload_status_string.restype = ctypes.c_char_p
+    seen = set()
+    for code in range(7):
+        s = lib.bload_status_string(code).decode()
+        assert s.startswith("BLOAD_")
+        seen.add(s)
+    assert len(seen) == 7
+    assert "unknown" in lib.bload_status_string(99).decode()
+
+
+def test_workspace_queries(lib):
+    lib.bload_plan_workspace_bytes.restype = ctypes.c_size_t
+    lib.bload_plan_workspace_bytes.argtypes = [ctypes.c_int64]
+    sizes = [lib.bload_plan_workspace_bytes(n) for n in (0, 1, 1000, 10**6)]
+    assert sizes == sorted(sizes) and sizes[-1] >= 21 * 10**6
+    assert all(s % 16 == 0 for s in sizes)
+    assert lib.bload_plan_workspace_bytes(-1) == 0
+    assert lib.bload_plan_workspace_bytes((1 << 27) + 1) == 0
+    f = lib.bload_segment_reduce_workspace_bytes
+    f.restype = ctypes.c_size_t
+    f.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int64, ctypes.c_int]
+    assert f(324084, 4096, 1, 3) == 0              # token blocks end on tile borders
+    assert f(34576, 3000, 80, 2) == 0              # one chunk per block
+    assert f(180, 600, 37632, 0) > 0               # video blocks are cut in time
+    assert f(0, 600, 8, 0) == 0 and f(5, 0, 8, 0) == 0 and f(5, 8, 8, 7) == 0
+
+
+def test_argument_checks_need_no_gpu(lib):
+    # every call below must be refused on the host, before any HIP call
+    vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+    nb, tot = i64(7), i64(7)
+    lib.bload_plan.restype = ctypes.c_int
+    lib.bload_plan.argtypes = [vp, i64, i32, ctypes.c_uint64, vp, vp, vp, vp,
+                               ctypes.POINTER(i64), ctypes.POINTER(i64), vp, ctypes.c_size_t, vp]
+    p = 0x1000                                      # never dereferenced by a refused call
+    assert lib.bload_plan(p, -1, 8, 0, p, p, p, p, nb, tot, p, 1 << 20, None) == 1
+    assert lib.bload_plan(p, 4, 0, 0, p, p, p, p, nb, tot, p, 1 << 20, None) == 1
+    assert lib.bload_plan(None, 4, 8, 0, p, p, p, p, nb, tot, p, 1 << 20, None) == 1
+    assert lib.bload_plan(p, 4, 8, 0, p, p, p, p, nb, tot, p, 8, None) == 3
+    assert lib.bload_plan(p, 4, 8, 0, p + 2, p, p, p, nb, tot, p, 1 << 20, None) == 4
+    assert lib.bload_plan(p, (1 << 27) + 1, 8, 0, p, p, p, p, nb, tot, p, 1 << 20, None) == 5
+    assert lib.bload_plan(p, 0, 8, 0, p, p, p, p, nb, tot, p, 0, None) == 0
+    assert (nb.value, tot.value) == (0, 0)
+    lib.bload_pack.restype = ctypes.c_int
+    lib.bload_pack.argtypes = [vp] * 7 + [i64, i64, i32, i64] + [vp] * 6
+    ok = [p] * 7 + [4, 2, 8, 16] + [p] * 5 + [None]
+    assert lib.bload_pack(*(ok[:7] + [4, 2, 0, 16] + ok[11:])) == 1          # t_blk < 1
+    assert lib.bload_pack(*(ok[:7] + [4, 2, 8, 0] + ok[11:])) == 1           # frame_bytes < 1
+    assert lib.bload_pack(*([None] + ok[1:])) == 1                           # null source
+    assert lib.bload_pack(*(ok[:11] + [p + 4] + ok[12:])) == 4               # packed misaligned
+    assert lib.bload_pack(*(ok[:7] + [0, 0, 8, 16] + ok[11:])) == 0          # nothing to do
+    lib.bload_segment_reduce.restype = ctypes.c_int
+    lib.bload_segment_reduce.argtypes = [vp, vp, vp, vp, i64, i32, i64, ctypes.c_int, ctypes.c_int,
+                                         i64, vp, vp, ctypes.c_size_t, vp]
+    assert lib.bload_segment_reduce(p, p, p, p, 2, 8, 4, 3, 1, 4, p, p, 1 << 20, None) == 1  # i32 mean
+    assert lib.bload_segment_reduce(p, p, p, p, 2, 8, 4, 9, 0, 4, p, p, 1 << 20, None) == 1
+    assert lib.bload_segment_reduce(p, p, p, p, 2, 8, 0, 0, 0, 4, p, p, 1 << 20, None) == 1
+    assert lib.bload_segment_reduce(p + 1, p, p, p, 2, 8, 4, 0, 0, 4, p, p, 1 << 20, None) == 4
+    assert lib.bload_segment_reduce(p, p, p, p, 50, 5000, 1, 2, 0, 4, p, p, 8, None) == 3
+    assert lib.bload_segment_reduce(p, p, p, p, 0, 8, 4, 0, 0, 4, p, p, 0, None) == 0
