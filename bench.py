@@ -52,6 +52,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain elementwise copy of 1 GiB (read 1 GiB, write 1 GiB) "
+                         "three times before the steps, as the known-size kernel that the "
+                         "rocprofv3 HBM counters are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the packer runs on a single MI355X and this build has "
@@ -100,6 +104,14 @@ def main() -> int:
                                    workspace=red_ws)
         if events:
             events[3].record()
+
+    if args.calibrate_copy:
+        a = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            torch.mul(a, 1.0, out=b)
+        torch.cuda.synchronize()
+        del a, b
 
     for _ in range(args.warmup):
         step()
