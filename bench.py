@@ -84,6 +84,8 @@ def main() -> int:
     plan = bload.bload_plan(d_L, T, seed, workspace=plan_ws)
     B = plan.num_blocks
     packed = bload.alloc_packed(B, T, F, dev)
+    pack_ws = torch.empty(max(16, bload.bload_pack_workspace_bytes(B, T, F)), dtype=torch.uint8,
+                          device=dev)
     red_ws = torch.empty(max(16, bload.bload_segment_reduce_workspace_bytes(B, T, D, w.dtype)),
                          dtype=torch.uint8, device=dev)
     red = torch.zeros((N, D), dtype=torch.int64 if w.dtype == "i32" else torch.float32, device=dev)
@@ -96,7 +98,7 @@ def main() -> int:
         bload.bload_plan(d_L, T, seed, workspace=plan_ws, out=plan)
         if events:
             events[1].record()
-        bload.bload_pack(d_src, d_so, d_L, plan, F, out=packed)
+        bload.bload_pack(d_src, d_so, d_L, plan, F, out=packed, workspace=pack_ws)
         if events:
             events[2].record()
         bload.bload_segment_reduce(packed.packed, packed.seq_id, packed.reset, packed.valid,

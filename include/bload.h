@@ -111,30 +111,40 @@ bload_status bload_plan(const int32_t* d_lengths, int64_t n_seq, int32_t t_blk, 
  *
  * d_src          in   bytes[total_frames * frame_bytes]: the ragged source, the
  *                     frames of sequence i stored contiguously from frame
- *                     d_src_offsets[i]; 16-byte aligned when frame_bytes % 16 == 0,
- *                     else aligned to the largest power of two <= 8 dividing frame_bytes
+ *                     d_src_offsets[i]; any byte alignment (fastest when it is
+ *                     16-byte aligned and frame_bytes is a multiple of 16)
  * d_src_offsets  in   int64[n_seq+1]  first source frame of each sequence;
  *                     src_offsets[i+1] - src_offsets[i] must equal L_i (not checked)
  * d_lengths, d_order, d_block_of_seq, d_offset_of_seq, d_block_first
  *                in   as produced by bload_plan for the same lengths
  * num_blocks     in   B as returned by bload_plan
- * d_packed       out  bytes[B, t_blk, frame_bytes], 16-byte aligned; slot
+ * d_packed       out  bytes[B, t_blk, frame_bytes]; slot
  *                     (b, offset_of_seq[i] + t) receives frame t of sequence i,
  *                     every other byte is 0
  * d_seq_id       out  int32[B, t_blk]  original sequence index, -1 on padding
  * d_frame_idx    out  int32[B, t_blk]  frame number inside its sequence, -1 on padding
  * d_reset        out  uint8[B, t_blk]  1 on the first frame of a sequence, else 0
  * d_valid        out  uint8[B, t_blk]  1 on a real frame, 0 on padding
+ *                     (all five outputs 16-byte aligned)
+ *
+ * d_workspace         device scratch of >= bload_pack_workspace_bytes(...) bytes,
+ *                     16-byte aligned (one int32 per 4 KiB of packed tensor when
+ *                     frame_bytes >= 512: where each destination tile starts in
+ *                     the shuffled order; 0 bytes for smaller frames, then the
+ *                     pointer may be NULL); contents meaningless afterwards
  *
  * Every byte of the five outputs is written exactly once (no prior memset is
  * needed).  Asynchronous on `hip_stream`.  n_seq = 0 / num_blocks = 0: no-op.
  */
+size_t bload_pack_workspace_bytes(int64_t num_blocks, int32_t t_blk, int64_t frame_bytes);
+
 bload_status bload_pack(const void* d_src, const int64_t* d_src_offsets, const int32_t* d_lengths,
                         const int32_t* d_order, const int32_t* d_block_of_seq,
                         const int32_t* d_offset_of_seq, const int32_t* d_block_first,
                         int64_t n_seq, int64_t num_blocks, int32_t t_blk, int64_t frame_bytes,
                         void* d_packed, int32_t* d_seq_id, int32_t* d_frame_idx,
-                        uint8_t* d_reset, uint8_t* d_valid, void* hip_stream);
+                        uint8_t* d_reset, uint8_t* d_valid,
+                        void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
 /* -------------------------------------------------------- segment reduce --
  * Methods section: knowing where a new sequence starts lets the consumer drop

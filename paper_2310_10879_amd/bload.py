@@ -42,9 +42,11 @@ _lib.bload_plan_workspace_bytes.argtypes = [_i64]
 _lib.bload_plan.restype = ctypes.c_int
 _lib.bload_plan.argtypes = [_vp, _i64, _i32, _u64, _vp, _vp, _vp, _vp,
                             ctypes.POINTER(_i64), ctypes.POINTER(_i64), _vp, _sz, _vp]
+_lib.bload_pack_workspace_bytes.restype = _sz
+_lib.bload_pack_workspace_bytes.argtypes = [_i64, _i32, _i64]
 _lib.bload_pack.restype = ctypes.c_int
 _lib.bload_pack.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i32, _i64,
-                            _vp, _vp, _vp, _vp, _vp, _vp]
+                            _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.bload_segment_reduce_workspace_bytes.restype = _sz
 _lib.bload_segment_reduce_workspace_bytes.argtypes = [_i64, _i32, _i64, ctypes.c_int]
 _lib.bload_segment_reduce.restype = ctypes.c_int
@@ -88,6 +90,10 @@ def _stream() -> int:
 
 def bload_plan_workspace_bytes(n_seq: int) -> int:
     return int(_lib.bload_plan_workspace_bytes(n_seq))
+
+
+def bload_pack_workspace_bytes(num_blocks: int, t_blk: int, frame_bytes: int) -> int:
+    return int(_lib.bload_pack_workspace_bytes(num_blocks, t_blk, frame_bytes))
 
 
 def bload_segment_reduce_workspace_bytes(num_blocks: int, t_blk: int, feat_dim: int,
@@ -151,7 +157,8 @@ def alloc_packed(num_blocks: int, t_blk: int, frame_bytes: int, device) -> Packe
 
 
 def bload_pack(src: torch.Tensor, src_offsets: torch.Tensor, lengths: torch.Tensor, plan: Plan,
-               frame_bytes: int, out: Packed | None = None) -> Packed:
+               frame_bytes: int, out: Packed | None = None,
+               workspace: torch.Tensor | None = None) -> Packed:
     """src: the ragged source (any dtype, contiguous, ``total_frames * frame_bytes`` bytes);
     src_offsets: int64[N+1].  Asynchronous on the current stream."""
     n = lengths.shape[0]
@@ -162,13 +169,17 @@ def bload_pack(src: torch.Tensor, src_offsets: torch.Tensor, lengths: torch.Tens
     if out.packed.numel() != plan.num_blocks * plan.t_blk * frame_bytes or \
             out.seq_id.numel() != plan.num_blocks * plan.t_blk:
         raise ValueError("output buffers do not match num_blocks * t_blk")
+    if workspace is None:
+        need = bload_pack_workspace_bytes(plan.num_blocks, plan.t_blk, frame_bytes)
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=lengths.device)
     st = _lib.bload_pack(_ptr(src), _ptr(src_offsets, torch.int64), _ptr(lengths, torch.int32),
                          _ptr(plan.order, torch.int32), _ptr(plan.block_of_seq, torch.int32),
                          _ptr(plan.offset_of_seq, torch.int32), _ptr(plan.block_first, torch.int32),
                          n, plan.num_blocks, plan.t_blk, frame_bytes,
                          _ptr(out.packed, torch.uint8), _ptr(out.seq_id, torch.int32),
                          _ptr(out.frame_idx, torch.int32), _ptr(out.reset, torch.uint8),
-                         _ptr(out.valid, torch.uint8), _stream())
+                         _ptr(out.valid, torch.uint8), _ptr(workspace),
+                         workspace.numel() * workspace.element_size(), _stream())
     _check(st)
     return out
 

@@ -9,9 +9,9 @@
 // thread, so no memset pass and no atomics are needed.
 //
 // Two tile shapes:
-//   wide   (frame_bytes >= 256): a tile is a flat byte range of the packed
-//          tensor; each sequence overlapping it is one long contiguous copy.
-//   narrow (frame_bytes <  256): a tile is 1024 consecutive slots; lanes take
+//   wide   (frame_bytes >= 512): a tile is a flat byte range of the packed
+//          tensor; each sequence overlapping it is one contiguous copy.
+//   narrow (frame_bytes <  512): a tile is 1024 consecutive slots; lanes take
 //          consecutive 16-byte destination vectors and assemble them from
 //          source elements of the widest type that divides the frame.
 #include "bload_common.hpp"
@@ -150,12 +150,30 @@ __device__ __forceinline__ int run_of_slot(const RunTable<MAXRUNS>& tab, int n, 
 }
 
 // ------------------------------------------------------------------- wide
+//
+// One workgroup writes one small flat piece of the packed tensor and ends:
+// workgroups that run at the same time then touch one compact window of the
+// destination (and a handful of source streams), which is what HBM wants; a
+// workgroup that loops over a large private tile does measurably worse.
+// To keep so short a workgroup cheap there is no LDS and no barrier here, and
+// the lookup of the tile's runs is wave-uniform (a binary search over the
+// block's positions followed by a walk over consecutive positions), so it
+// runs on the scalar unit with a handful of dependent scalar loads.
 
-constexpr int kWideTileMax = 65536;                 // bytes of packed tensor per workgroup
-constexpr int kWideMinFrame = 256;                  // smallest frame the wide kernel takes
-constexpr int kWideMaxRuns = kWideTileMax / kWideMinFrame + 2;
+constexpr int kWideMinFrame = 512;                  // smallest frame the wide kernel takes
+constexpr int kWideTile = 4096;                     // tile used: one 16-byte vector per thread
 
 typedef vec16 __attribute__((aligned(1))) vec16_unaligned;
+
+// floor(x / d) for 0 <= x < 2^52, d >= 1, with inv_d = 1.0 / d: the double
+// quotient is within one of the answer, fixed up exactly in integers.
+__device__ __forceinline__ int64_t floor_div(int64_t x, int64_t d, double inv_d)
+{
+    int64_t q = (int64_t)((double)x * inv_d);
+    if (q * d > x) --q;
+    else if ((q + 1) * d <= x) ++q;
+    return q;
+}
 
 // Write packed bytes [lo, hi): copies of src[0 ..) (any alignment) or zeros.
 // Destination vectors are 16-byte aligned; the ragged ends of the range are
@@ -205,51 +223,138 @@ __device__ __forceinline__ void write_range(uint8_t* packed, int64_t lo, int64_t
     }
 }
 
-__global__ __launch_bounds__(kThreads) void pack_wide_kernel(PackArgs a, int32_t tile_bytes)
+// Start-table entries of global slots [lo, hi) (fewer than 64): lane k of the
+// calling wave writes slot lo + k.  frame0 = frame index of slot lo, or -1 for padding.
+__device__ __forceinline__ void write_slots(const PackArgs& a, int64_t lo, int64_t hi, int32_t seq,
+                                            int64_t frame0)
 {
-    __shared__ RunTable<kWideMaxRuns> tab;
-    const int tid = (int)threadIdx.x;
-    const int64_t F = a.frame_bytes;
-    const int64_t total_bytes = a.total_slots * F;
-    const int64_t D0 = (int64_t)blockIdx.x * tile_bytes;
-    const int64_t D1 = min(D0 + (int64_t)tile_bytes, total_bytes);
-    const int64_t gs_lo = D0 / F;                    // first slot touched
-    const int64_t gs_hi = (D1 + F - 1) / F;          // one past the last slot touched
-
-    if (wave_id() == 0) find_runs(a, gs_lo, gs_hi, tab);
-    __syncthreads();
-    const int n = tab.n;
-
-    // payload: runs in order, zeros in the gaps (block tails)
-    int64_t cursor = D0;
-    for (int r = 0; r < n; ++r) {
-        const int64_t run_lo = (gs_lo + tab.dst[r]) * F;
-        const int64_t run_hi = run_lo + (int64_t)tab.len[r] * F;
-        const int64_t lo = max(max(run_lo, D0), cursor);
-        const int64_t hi = min(run_hi, D1);
-        if (hi <= lo) continue;
-        if (lo > cursor) write_range<true>(a.packed, cursor, lo, nullptr);
-        write_range<false>(a.packed, lo, hi, a.src + tab.src[r] * F + (lo - run_lo));
-        cursor = hi;
-    }
-    if (cursor < D1) write_range<true>(a.packed, cursor, D1, nullptr);
-
-    // start table of the slots whose first byte lies in this tile
-    const int64_t m_lo = gs_lo + ((gs_lo * F < D0) ? 1 : 0);
-    const int64_t m_hi = min(gs_hi, a.total_slots);
-    for (int64_t g = m_lo + tid; g < m_hi; g += kThreads) {
-        const int32_t slot = (int32_t)(g - gs_lo);
-        const int r = run_of_slot(tab, n, slot);
-        int32_t sid = -1, fid = -1;
-        if (r >= 0) {
-            const int64_t t = (int64_t)slot - tab.dst[r];
-            if (t < tab.len[r]) { sid = tab.seq[r]; fid = (int32_t)t; }
-        }
-        a.seq_id[g] = sid;
+    const int64_t g = lo + lane_id();
+    if (g < hi) {
+        const int32_t fid = frame0 < 0 ? -1 : (int32_t)(frame0 + lane_id());
+        a.seq_id[g] = frame0 < 0 ? -1 : seq;
         a.frame_idx[g] = fid;
         a.reset[g] = (uint8_t)(fid == 0);
         a.valid[g] = (uint8_t)(fid >= 0);
     }
+}
+
+// Pass 1: for every tile, the last shuffled position of the tile's first block
+// whose sequence starts at or before the tile's first slot (the block's first
+// sequence starts at slot 0, so there is one).  One thread per tile.
+__global__ __launch_bounds__(kThreads) void pack_wide_locate_kernel(
+    const int32_t* __restrict__ order, const int32_t* __restrict__ offset_of_seq,
+    const int32_t* __restrict__ block_first, int32_t n_seq, int64_t t_blk, int64_t frame_bytes,
+    int64_t n_tiles, int32_t tile_bytes, double inv_frame_bytes, double inv_t_blk,
+    int32_t* __restrict__ first_pos)
+{
+    const int64_t tile = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (tile >= n_tiles) return;
+    const int64_t gs_lo = floor_div(tile * tile_bytes, frame_bytes, inv_frame_bytes);
+    const int64_t b0 = floor_div(gs_lo, t_blk, inv_t_blk);
+    const int32_t rel = (int32_t)(gs_lo - b0 * t_blk);
+    int32_t p = min(max(block_first[b0], 0), n_seq);
+    int32_t above = min(max(block_first[b0 + 1], p), n_seq);
+    while (above - p > 1) {
+        const int32_t mid = p + ((above - p) >> 1);
+        const uint32_t i = (uint32_t)order[mid];
+        if (i < (uint32_t)n_seq && offset_of_seq[i] <= rel) p = mid; else above = mid;
+    }
+    first_pos[tile] = p;
+}
+
+// Pass 2: the copy.  The lookup tables come as separate __restrict__ pointers
+// (not inside PackArgs) so that the compiler knows nothing this kernel stores
+// can alias them and keeps their loads on the scalar unit.
+__global__ __launch_bounds__(kThreads) void pack_wide_kernel(
+    PackArgs a, const int64_t* __restrict__ src_offsets, const int32_t* __restrict__ lengths,
+    const int32_t* __restrict__ order, const int32_t* __restrict__ block_of_seq,
+    const int32_t* __restrict__ offset_of_seq, const int32_t* __restrict__ first_pos,
+    int32_t tile_bytes, double inv_frame_bytes)
+{
+    const int64_t F = a.frame_bytes;
+    const int64_t T = a.t_blk;
+    const int32_t n_seq = a.n_seq;
+    const int64_t total_bytes = a.total_slots * F;
+    const int64_t D0 = (int64_t)blockIdx.x * tile_bytes;
+    const int64_t D1 = min(D0 + (int64_t)tile_bytes, total_bytes);
+    const bool table_wave = wave_id() == 0;
+    int32_t p = min(max(first_pos[blockIdx.x], 0), n_seq);
+
+    // the common case first: the tile lies inside one run -- one load and one
+    // store per thread, plus the start-table entries of the few frames that
+    // begin in the tile
+    if (p < n_seq && tile_bytes == kThreads * 16) {
+        const uint32_t i = (uint32_t)order[p];
+        if (i < (uint32_t)n_seq) {
+            const int64_t g = (int64_t)block_of_seq[i] * T + offset_of_seq[i];
+            const int64_t len = lengths[i];
+            const int64_t run_lo = g * F;
+            if (run_lo <= D0 && run_lo + len * F >= D0 + tile_bytes && D0 + tile_bytes <= total_bytes) {
+                const uint8_t* s = a.src + src_offsets[i] * F + (D0 - run_lo) + 16 * (int64_t)threadIdx.x;
+                const vec16 x = __builtin_nontemporal_load(reinterpret_cast<const vec16_unaligned*>(s));
+                store_stream(reinterpret_cast<vec16*>(a.packed + D0) + threadIdx.x, x);
+                if (table_wave) {
+                    // frames t of this run with D0 <= run_lo + t * F < D1
+                    const int64_t t = floor_div(D0 - run_lo + F - 1, F, inv_frame_bytes) + lane_id();
+                    if (run_lo + t * F < D1 && t < len) {
+                        a.seq_id[g + t] = (int32_t)i;
+                        a.frame_idx[g + t] = (int32_t)t;
+                        a.reset[g + t] = (uint8_t)(t == 0);
+                        a.valid[g + t] = 1;
+                    }
+                }
+                return;
+            }
+            // next most common: the tile lies in the zero tail of the run's block
+            if (run_lo + len * F <= D0 && ((int64_t)block_of_seq[i] + 1) * T * F >= D0 + tile_bytes) {
+                const vec16 z = {0u, 0u, 0u, 0u};
+                store_stream(reinterpret_cast<vec16*>(a.packed + D0) + threadIdx.x, z);
+                if (table_wave) {
+                    const int64_t slot = floor_div(D0 + F - 1, F, inv_frame_bytes) + lane_id();
+                    if (slot * F < D1) {
+                        a.seq_id[slot] = -1;
+                        a.frame_idx[slot] = -1;
+                        a.reset[slot] = 0;
+                        a.valid[slot] = 0;
+                    }
+                }
+                return;
+            }
+        }
+    }
+
+    const int64_t gs_lo = floor_div(D0, F, inv_frame_bytes);              // first slot touched
+    const int64_t gs_hi = floor_div(D1 + F - 1, F, inv_frame_bytes);      // one past the last
+    // slots whose first byte lies in this tile get their start-table entry here
+    const int64_t m_lo = gs_lo + ((gs_lo * F < D0) ? 1 : 0);
+    const int64_t m_hi = min(gs_hi, a.total_slots);
+
+    // runs in destination order from there on, zeros in the gaps (block tails)
+    int64_t cursor = D0;          // payload bytes written so far
+    int64_t mcursor = m_lo;       // start-table slots written so far
+    for (; p < n_seq; ++p) {
+        const uint32_t i = (uint32_t)order[p];
+        if (i >= (uint32_t)n_seq) break;
+        const int64_t g = (int64_t)block_of_seq[i] * T + offset_of_seq[i];
+        if (g >= gs_hi) break;
+        const int64_t len = lengths[i];
+        if (g + len <= gs_lo) continue;           // ends before the tile: the tile starts in padding
+        const int64_t run_lo = g * F;
+        const int64_t lo = max(max(run_lo, D0), cursor);
+        const int64_t hi = min(run_lo + len * F, D1);
+        if (hi > lo) {
+            if (lo > cursor) write_range<true>(a.packed, cursor, lo, nullptr);
+            write_range<false>(a.packed, lo, hi, a.src + src_offsets[i] * F + (lo - run_lo));
+            cursor = hi;
+        }
+        if (table_wave) {
+            const int64_t s_lo = max(g, mcursor), s_hi = min(g + len, m_hi);
+            if (s_lo > mcursor) write_slots(a, mcursor, s_lo, -1, -1);
+            if (s_hi > s_lo) { write_slots(a, s_lo, s_hi, (int32_t)i, s_lo - g); mcursor = s_hi; }
+        }
+    }
+    if (cursor < D1) write_range<true>(a.packed, cursor, D1, nullptr);
+    if (table_wave && mcursor < m_hi) write_slots(a, mcursor, m_hi, -1, -1);
 }
 
 // ----------------------------------------------------------------- narrow
@@ -338,7 +443,7 @@ __global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a)
     // from elements of type E (k elements per frame)
     constexpr int EPV = 16 / (int)sizeof(E);
     const int32_t k = (int32_t)(a.frame_bytes / (int64_t)sizeof(E));
-    const int32_t tile_elems = nslot * k;                       // < 1024 * 256
+    const int32_t tile_elems = nslot * k;                       // < 1024 * 512
     const int32_t nvec = (tile_elems + EPV - 1) / EPV;
     const E* src = reinterpret_cast<const E*>(a.src);
     uint8_t* dst_tile = a.packed + g0 * a.frame_bytes;          // 16-byte aligned
@@ -371,13 +476,22 @@ __global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a)
 
 using namespace bload;
 
+extern "C" size_t bload_pack_workspace_bytes(int64_t num_blocks, int32_t t_blk, int64_t frame_bytes)
+{
+    if (num_blocks <= 0 || t_blk < 1 || frame_bytes < kWideMinFrame) return 0;
+    const int64_t total_slots = num_blocks * (int64_t)t_blk;
+    if (total_slots >= ((int64_t)1 << 40) || total_slots > (((int64_t)1 << 52) - 1) / frame_bytes) return 0;
+    return round_up((size_t)ceil_div(total_slots * frame_bytes, kWideTile) * sizeof(int32_t), 16);
+}
+
 extern "C" bload_status bload_pack(const void* d_src, const int64_t* d_src_offsets,
                                    const int32_t* d_lengths, const int32_t* d_order,
                                    const int32_t* d_block_of_seq, const int32_t* d_offset_of_seq,
                                    const int32_t* d_block_first, int64_t n_seq, int64_t num_blocks,
                                    int32_t t_blk, int64_t frame_bytes, void* d_packed,
                                    int32_t* d_seq_id, int32_t* d_frame_idx, uint8_t* d_reset,
-                                   uint8_t* d_valid, void* hip_stream)
+                                   uint8_t* d_valid, void* d_workspace, size_t workspace_bytes,
+                                   void* hip_stream)
 {
     if (n_seq < 0 || num_blocks < 0 || t_blk < 1 || frame_bytes < 1) return BLOAD_EINVAL;
     if (n_seq > BLOAD_MAX_SEQ || num_blocks > n_seq) return n_seq > BLOAD_MAX_SEQ ? BLOAD_EOVERFLOW
@@ -418,14 +532,22 @@ extern "C" bload_status bload_pack(const void* d_src, const int64_t* d_src_offse
 
     if (frame_bytes >= kWideMinFrame) {
         const int64_t total_bytes = total_slots * frame_bytes;
-        // 64 KiB tiles; smaller ones when the tensor is small, so that the
-        // launch still has a few thousand workgroups
-        int32_t tile_bytes = kWideTileMax;
-        while (tile_bytes > 4096 && total_bytes / tile_bytes < 4096) tile_bytes >>= 1;
+        if (total_bytes >= ((int64_t)1 << 52)) return BLOAD_EOVERFLOW;
+        const int32_t tile_bytes = kWideTile;
         const int64_t tiles = ceil_div(total_bytes, tile_bytes);
         if (tiles > INT32_MAX) return BLOAD_EOVERFLOW;
+        if (!d_workspace) return BLOAD_EINVAL;
+        if (!aligned_to(d_workspace, 16)) return BLOAD_EALIGN;
+        if (workspace_bytes < (size_t)tiles * sizeof(int32_t)) return BLOAD_EWORKSPACE;
+        int32_t* first_pos = static_cast<int32_t*>(d_workspace);
+        const double inv_frame = 1.0 / (double)frame_bytes, inv_t = 1.0 / (double)t_blk;
+        hipLaunchKernelGGL(pack_wide_locate_kernel, dim3((uint32_t)ceil_div(tiles, kThreads)),
+                           dim3(kThreads), 0, stream, d_order, d_offset_of_seq, d_block_first,
+                           (int32_t)n_seq, (int64_t)t_blk, frame_bytes, tiles, tile_bytes, inv_frame,
+                           inv_t, first_pos);
         hipLaunchKernelGGL(pack_wide_kernel, dim3((uint32_t)tiles), dim3(kThreads), 0, stream, a,
-                           tile_bytes);
+                           d_src_offsets, d_lengths, d_order, d_block_of_seq, d_offset_of_seq,
+                           first_pos, tile_bytes, inv_frame);
     } else {
         const int64_t tiles = ceil_div(total_slots, kNarrowSlots);
         if (tiles > INT32_MAX) return BLOAD_EOVERFLOW;

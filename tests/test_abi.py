@@ -29,7 +29,8 @@ def lib():
 def test_header_declares_the_three_entry_points():
     names = declared_functions()
     for must in ("bload_plan", "bload_pack", "bload_segment_reduce", "bload_plan_workspace_bytes",
-                 "bload_segment_reduce_workspace_bytes", "bload_status_string"):
+                 "bload_pack_workspace_bytes", "bload_segment_reduce_workspace_bytes",
+                 "bload_status_string"):
         assert must in names
 
 
@@ -83,13 +84,20 @@ def test_argument_checks_need_no_gpu(lib):
     assert lib.bload_plan(p, 0, 8, 0, p, p, p, p, nb, tot, p, 0, None) == 0
     assert (nb.value, tot.value) == (0, 0)
     lib.bload_pack.restype = ctypes.c_int
-    lib.bload_pack.argtypes = [vp] * 7 + [i64, i64, i32, i64] + [vp] * 6
-    ok = [p] * 7 + [4, 2, 8, 16] + [p] * 5 + [None]
+    lib.bload_pack.argtypes = [vp] * 7 + [i64, i64, i32, i64] + [vp] * 6 + [ctypes.c_size_t, vp]
+    ok = [p] * 7 + [4, 2, 8, 16] + [p] * 5 + [p, 1 << 20, None]
     assert lib.bload_pack(*(ok[:7] + [4, 2, 0, 16] + ok[11:])) == 1          # t_blk < 1
     assert lib.bload_pack(*(ok[:7] + [4, 2, 8, 0] + ok[11:])) == 1           # frame_bytes < 1
     assert lib.bload_pack(*([None] + ok[1:])) == 1                           # null source
     assert lib.bload_pack(*(ok[:11] + [p + 4] + ok[12:])) == 4               # packed misaligned
     assert lib.bload_pack(*(ok[:7] + [0, 0, 8, 16] + ok[11:])) == 0          # nothing to do
+    assert lib.bload_pack(*(ok[:7] + [4, 2, 8, 4096] + ok[11:16] + [p, 8, None])) == 3   # workspace
+    f = lib.bload_pack_workspace_bytes
+    f.restype = ctypes.c_size_t
+    f.argtypes = [i64, i32, i64]
+    need = 4 * -(-180 * 600 * 37632 // 4096)         # one int32 per 4 KiB tile
+    assert need <= f(180, 600, 37632) < need + 16 and f(180, 600, 37632) % 16 == 0
+    assert f(180, 600, 4) == 0 and f(0, 600, 4096) == 0
     lib.bload_segment_reduce.restype = ctypes.c_int
     lib.bload_segment_reduce.argtypes = [vp, vp, vp, vp, i64, i32, i64, ctypes.c_int, ctypes.c_int,
                                          i64, vp, vp, ctypes.c_size_t, vp]
