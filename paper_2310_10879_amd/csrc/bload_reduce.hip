@@ -55,6 +55,7 @@ struct ReduceArgs {
     int32_t n_chunks;        // wide: chunks per block
     int32_t row_lanes_log2;  // wide: lanes per row = 1 << this
     int32_t n_vec;           // wide: lanes needed to cover one frame
+    int32_t feat_tiles;      // wide: workgroups side by side over one frame
     // partial buffers (null when no chunk border can cut a segment)
     ChunkDesc* desc;         // [total_chunks]
     void* head_part;         // [total_chunks, feat_dim] accumulators
@@ -110,8 +111,33 @@ __device__ __forceinline__ float finish<float>(float sum, int32_t cnt, int mean)
 
 // ------------------------------------------------------------------- wide
 
-constexpr int kWideUnroll = 4;
+constexpr int kWideUnroll = 8;
 constexpr int kWideFlagBytes = 32768;      // LDS budget for the staged flags
+
+// First slot s in [t, len) whose staged flags say "valid" (WANT_VALID) or "not a
+// plain continuation: padding or a start flag" (!WANT_VALID); len if none.  The
+// lanes of a row (or of the wave, for rows wider than a wave) test one slot
+// each per step and vote; every lane of the row gets the same answer.
+template <bool WANT_VALID>
+__device__ __forceinline__ int32_t next_slot(const uint8_t* flags, int32_t t, int32_t len,
+                                             int row_lanes_log2)
+{
+    const int width = row_lanes_log2 >= 6 ? kWave : (1 << row_lanes_log2);
+    const int lane = lane_id();
+    const int base = lane & ~(width - 1);
+    const uint64_t row_mask = (width == kWave ? ~0ull : ((1ull << width) - 1ull)) << base;
+    for (; t < len; t += width) {
+        const int32_t s = t + (lane - base);
+        bool hit = false;
+        if (s < len) {
+            const uint8_t f = flags[s];
+            hit = WANT_VALID ? (f & 1) != 0 : (f & 3) != 1;
+        }
+        const uint64_t vote = __ballot(hit) & row_mask;
+        if (vote) return t + (__ffsll((unsigned long long)vote) - 1 - base);
+    }
+    return len;
+}
 
 template <typename ElemT, int VEC>
 __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
@@ -121,7 +147,10 @@ __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
     const int tid = (int)threadIdx.x;
     const int C = a.chunk, stride = C + 1;
     const int rows = kThreads >> a.row_lanes_log2;
-    const int64_t q_base = (int64_t)blockIdx.x * rows;
+    // consecutive workgroups take the lane-slices of one frame range, so that
+    // workgroups running side by side read neighbouring memory
+    const int feat_tile = (int)(blockIdx.x % (uint32_t)a.feat_tiles);
+    const int64_t q_base = (int64_t)(blockIdx.x / (uint32_t)a.feat_tiles) * rows;
     const int64_t T = a.t_blk;
 
     // stage the flags of this workgroup's chunks, plus the slot after each chunk
@@ -143,8 +172,12 @@ __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
     const int row = tid >> a.row_lanes_log2;
     const int col = tid & ((1 << a.row_lanes_log2) - 1);
     const int64_t q = q_base + row;
-    const int fv = (int)blockIdx.y * (1 << a.row_lanes_log2) + col;    // which lane-slice of the frame
-    if (q >= a.total_chunks || fv >= a.n_vec) return;
+    if (q >= a.total_chunks) return;
+    // which lane-slice of the frame; the surplus lanes of a row stay alive (they
+    // take part in the votes of next_slot), read what the last lane reads, and store nothing
+    const int fv_raw = feat_tile * (1 << a.row_lanes_log2) + col;
+    const bool lane_stores = fv_raw < a.n_vec;
+    const int fv = lane_stores ? fv_raw : a.n_vec - 1;
 
     const int64_t b = q / a.n_chunks;
     const int32_t t0 = (int32_t)(q - b * a.n_chunks) * C;
@@ -154,79 +187,86 @@ __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
     const int64_t frame_bytes = (int64_t)a.feat_dim * (int64_t)sizeof(ElemT);
     const uint8_t* lane_src = a.packed + g * frame_bytes + (int64_t)fv * VEC * (int64_t)sizeof(ElemT);
     const int64_t feat0 = (int64_t)fv * VEC;
-    const bool writes_desc = (col == 0 && blockIdx.y == 0 && a.desc != nullptr);
+    const bool writes_desc = (col == 0 && feat_tile == 0 && a.desc != nullptr);
     typedef typename OutOf<Acc>::T Out;
     Out* out = static_cast<Out*>(a.out);
     Acc* head_part = static_cast<Acc*>(a.head_part);
     Acc* tail_part = static_cast<Acc*>(a.tail_part);
 
     Acc acc[VEC];
-    bool open = false, head_open = false;
-    int32_t cnt = 0, last = 0;
     ChunkDesc desc{kHeadNone, 0, 0, -1};
 
-    // close the piece that is being accumulated; `closed` = the segment ends here
-    auto flush = [&](bool closed) {
-        if (head_open) {
-            if (head_part) {
+    // The chunk is a sequence of pieces: maximal runs of valid slots that hold
+    // no start flag after their first slot.  Find a piece [t, e) from the
+    // staged flags, sum it with unconditional loads, hand the sum on.
+    int32_t t = 0;
+    for (;;) {
+        t = next_slot<true>(flags, t, len, a.row_lanes_log2);           // next valid slot
+        if (t >= len) break;
+        const bool starts = (flags[t] & 2) || (t0 + t == 0);
+        // a valid first slot without a start flag continues the previous chunk's segment
+        const bool head_open = !starts && t == 0;
+        const int32_t e = next_slot<false>(flags, t + 1, len, a.row_lanes_log2);  // padding or a start
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) head_part[q * a.feat_dim + feat0 + e] = acc[e];
+        for (int k = 0; k < VEC; ++k) acc[k] = 0;
+        const uint8_t* p = lane_src + (int64_t)t * frame_bytes;
+        int32_t s = t;
+        for (; s + kWideUnroll <= e; s += kWideUnroll) {
+            LaneData<ElemT, VEC> x[kWideUnroll];
+#pragma unroll
+            for (int u = 0; u < kWideUnroll; ++u) x[u].load(p + (int64_t)u * frame_bytes);
+#pragma unroll
+            for (int u = 0; u < kWideUnroll; ++u) {
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) acc[k] += Elem<ElemT>::get(x[u].u.e[k]);
+            }
+            p += (int64_t)kWideUnroll * frame_bytes;
+        }
+        if (s < e) {
+            // the last, partial batch: all loads are issued at once as well (those
+            // past the piece re-read its last slot and are not added)
+            const int32_t left = e - s;
+            LaneData<ElemT, VEC> x[kWideUnroll];
+#pragma unroll
+            for (int u = 0; u < kWideUnroll; ++u)
+                x[u].load(p + (int64_t)min(u, left - 1) * frame_bytes);
+#pragma unroll
+            for (int u = 0; u < kWideUnroll; ++u) {
+                if (u < left) {
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k) acc[k] += Elem<ElemT>::get(x[u].u.e[k]);
+                }
+            }
+        }
+        const int32_t cnt = e - t;
+        // the segment ends here unless the piece runs to the chunk's end and the
+        // slot after the chunk (flags[len], 0 past the block) continues it
+        const bool closed = e < len || (flags[len] & 3) != 1;
+        if (head_open) {
+            if (head_part && lane_stores) {
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) head_part[q * a.feat_dim + feat0 + k] = acc[k];
             }
             desc.head_state = closed ? kHeadClosed : kHeadThrough;
             desc.cnt_head = cnt;
         } else {
-            const int32_t seq = a.seq_id[g + last];
+            const int32_t seq = a.seq_id[g + t];
             if (closed) {
-                if ((uint32_t)seq < (uint32_t)a.n_seq) {
+                if ((uint32_t)seq < (uint32_t)a.n_seq && lane_stores) {
 #pragma unroll
-                    for (int e = 0; e < VEC; ++e)
-                        out[(int64_t)seq * a.feat_dim + feat0 + e] = finish<Acc>(acc[e], cnt, a.mean);
+                    for (int k = 0; k < VEC; ++k)
+                        out[(int64_t)seq * a.feat_dim + feat0 + k] = finish<Acc>(acc[k], cnt, a.mean);
                 }
             } else {
-                if (tail_part) {
+                if (tail_part && lane_stores) {
 #pragma unroll
-                    for (int e = 0; e < VEC; ++e) tail_part[q * a.feat_dim + feat0 + e] = acc[e];
+                    for (int k = 0; k < VEC; ++k) tail_part[q * a.feat_dim + feat0 + k] = acc[k];
                 }
                 desc.cnt_tail = cnt;
                 desc.seq_tail = seq;
             }
         }
-    };
-
-    for (int32_t t = 0; t < len; t += kWideUnroll) {
-        LaneData<ElemT, VEC> x[kWideUnroll];
-        uint8_t f[kWideUnroll];
-#pragma unroll
-        for (int u = 0; u < kWideUnroll; ++u) {
-            f[u] = (t + u < len) ? flags[t + u] : (uint8_t)0;
-            if (f[u] & 1) x[u].load(lane_src + (int64_t)(t + u) * frame_bytes);
-        }
-#pragma unroll
-        for (int u = 0; u < kWideUnroll; ++u) {
-            if (t + u >= len) break;
-            if (!(f[u] & 1)) {                     // padding ends whatever was open
-                if (open) { flush(true); open = false; }
-                continue;
-            }
-            const bool starts = (f[u] & 2) || (t0 + t + u == 0);
-            if (starts || !open) {
-                if (open) flush(true);
-                // a valid slot without a start flag continues the previous chunk's segment
-                head_open = !starts && (t + u == 0);
-                open = true;
-                cnt = 0;
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) acc[e] = 0;
-            }
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[e] += Elem<ElemT>::get(x[u].u.e[e]);
-            cnt += 1;
-            last = t + u;
-        }
-    }
-    if (open) {
-        const uint8_t nf = flags[len];             // the slot after the chunk (0 past the block)
-        flush(!(nf & 1) || (nf & 2));
+        t = e;
     }
     if (writes_desc) a.desc[q] = desc;
 }
@@ -514,8 +554,7 @@ template <typename ElemT>
 static void launch_wide(const ReducePlan& p, const ReduceArgs& a, hipStream_t stream)
 {
     const int rows = kThreads >> p.row_lanes_log2;
-    const dim3 grid((uint32_t)ceil_div(p.total_chunks, rows),
-                    (uint32_t)ceil_div(p.n_vec, 1 << p.row_lanes_log2));
+    const dim3 grid((uint32_t)(ceil_div(p.total_chunks, rows) * a.feat_tiles));
     const size_t lds = (size_t)rows * (size_t)(p.chunk + 1);
     if (p.vec > 1)
         hipLaunchKernelGGL((reduce_wide_kernel<ElemT, 16 / (int)sizeof(ElemT)>), grid, dim3(kThreads),
@@ -573,7 +612,9 @@ extern "C" bload_status bload_segment_reduce(const void* d_packed, const int32_t
 
     const ReducePlan p = reduce_plan(num_blocks, t_blk, feat_dim, dtype);
     if (p.total_chunks * ceil_div(feat_dim, kThreads) > INT32_MAX) return BLOAD_EOVERFLOW;
-    if (p.wide && ceil_div(p.n_vec, 1 << p.row_lanes_log2) > 65535) return BLOAD_EOVERFLOW;
+    if (p.wide && ceil_div(p.total_chunks, kThreads >> p.row_lanes_log2) *
+                      ceil_div(p.n_vec, 1 << p.row_lanes_log2) > INT32_MAX)
+        return BLOAD_EOVERFLOW;
     if (p.partials) {
         if (!d_workspace) return BLOAD_EINVAL;
         if (!aligned_to(d_workspace, 16)) return BLOAD_EALIGN;
@@ -597,6 +638,7 @@ extern "C" bload_status bload_segment_reduce(const void* d_packed, const int32_t
     a.n_chunks = p.n_chunks;
     a.row_lanes_log2 = p.row_lanes_log2;
     a.n_vec = p.n_vec;
+    a.feat_tiles = p.wide ? (int32_t)ceil_div(p.n_vec, 1 << p.row_lanes_log2) : 1;
     if (p.partials) {
         uint8_t* ws = static_cast<uint8_t*>(d_workspace);
         a.desc = reinterpret_cast<ChunkDesc*>(ws + p.desc_off);
