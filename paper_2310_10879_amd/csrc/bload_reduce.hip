@@ -139,6 +139,37 @@ __device__ __forceinline__ int32_t next_slot(const uint8_t* flags, int32_t t, in
     return len;
 }
 
+// Store the VEC accumulators of every lane of a row to dst[feat0 ...].  A lane
+// holds VEC consecutive features, so storing straight from the registers
+// writes 16-byte pieces 16 * VEC bytes apart; when a whole wave belongs to one
+// row the values go through the wave's LDS scratch instead and leave as runs
+// of 64 consecutive elements.  `scratch` is null for rows narrower than a wave.
+template <typename Acc, int VEC>
+__device__ __forceinline__ void store_row(Acc* dst_row, int64_t feat0, const Acc (&v)[VEC],
+                                          bool lane_stores, Acc* scratch, int64_t wave_feat0,
+                                          int32_t feat_dim)
+{
+    if (VEC == 1 || scratch == nullptr) {
+        if (lane_stores) {
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) dst_row[feat0 + k] = v[k];
+        }
+        return;
+    }
+    const int lane = lane_id();
+    // element e of the wave's 64 * VEC span lives in lane e / VEC, register e % VEC
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) scratch[lane * (VEC + 1) + k] = v[k];
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+        const int e = j * kWave + lane;
+        const Acc x = scratch[(e / VEC) * (VEC + 1) + (e % VEC)];
+        if (wave_feat0 + e < feat_dim) dst_row[wave_feat0 + e] = x;
+    }
+    __builtin_amdgcn_wave_barrier();
+}
+
 template <typename ElemT, int VEC>
 __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
 {
@@ -193,6 +224,15 @@ __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
     Acc* head_part = static_cast<Acc*>(a.head_part);
     Acc* tail_part = static_cast<Acc*>(a.tail_part);
 
+    // per-wave LDS scratch for the transposed stores (behind the flags), when a
+    // wave lies inside one row
+    Acc* scratch = nullptr;
+    const int64_t wave_feat0 = (int64_t)(fv_raw - lane_id()) * VEC;   // first feature of the wave
+    if (VEC > 1 && a.row_lanes_log2 >= 6) {
+        const size_t flag_bytes = ((size_t)rows * stride + 15) & ~(size_t)15;
+        scratch = reinterpret_cast<Acc*>(s_flags + flag_bytes) + (size_t)wave_id() * kWave * (VEC + 1);
+    }
+
     Acc acc[VEC];
     ChunkDesc desc{kHeadNone, 0, 0, -1};
 
@@ -243,25 +283,19 @@ __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
         // slot after the chunk (flags[len], 0 past the block) continues it
         const bool closed = e < len || (flags[len] & 3) != 1;
         if (head_open) {
-            if (head_part && lane_stores) {
-#pragma unroll
-                for (int k = 0; k < VEC; ++k) head_part[q * a.feat_dim + feat0 + k] = acc[k];
-            }
+            if (head_part) store_row<Acc, VEC>(head_part + q * a.feat_dim, feat0, acc, lane_stores, scratch, wave_feat0, a.feat_dim);
             desc.head_state = closed ? kHeadClosed : kHeadThrough;
             desc.cnt_head = cnt;
         } else {
             const int32_t seq = a.seq_id[g + t];
             if (closed) {
-                if ((uint32_t)seq < (uint32_t)a.n_seq && lane_stores) {
+                if ((uint32_t)seq < (uint32_t)a.n_seq) {
 #pragma unroll
-                    for (int k = 0; k < VEC; ++k)
-                        out[(int64_t)seq * a.feat_dim + feat0 + k] = finish<Acc>(acc[k], cnt, a.mean);
+                    for (int k = 0; k < VEC; ++k) acc[k] = finish<Acc>(acc[k], cnt, a.mean);
+                    store_row<Acc, VEC>(out + (int64_t)seq * a.feat_dim, feat0, acc, lane_stores, scratch, wave_feat0, a.feat_dim);
                 }
             } else {
-                if (tail_part && lane_stores) {
-#pragma unroll
-                    for (int k = 0; k < VEC; ++k) tail_part[q * a.feat_dim + feat0 + k] = acc[k];
-                }
+                if (tail_part) store_row<Acc, VEC>(tail_part + q * a.feat_dim, feat0, acc, lane_stores, scratch, wave_feat0, a.feat_dim);
                 desc.cnt_tail = cnt;
                 desc.seq_tail = seq;
             }
@@ -555,7 +589,10 @@ static void launch_wide(const ReducePlan& p, const ReduceArgs& a, hipStream_t st
 {
     const int rows = kThreads >> p.row_lanes_log2;
     const dim3 grid((uint32_t)(ceil_div(p.total_chunks, rows) * a.feat_tiles));
-    const size_t lds = (size_t)rows * (size_t)(p.chunk + 1);
+    size_t lds = (size_t)rows * (size_t)(p.chunk + 1);
+    if (p.vec > 1 && p.row_lanes_log2 >= 6)     // + the per-wave scratch of the transposed stores
+        lds = round_up(lds, 16) + (size_t)(kThreads / kWave) * kWave * (p.vec + 1) *
+                                      sizeof(typename Elem<ElemT>::Acc);
     if (p.vec > 1)
         hipLaunchKernelGGL((reduce_wide_kernel<ElemT, 16 / (int)sizeof(ElemT)>), grid, dim3(kThreads),
                            lds, stream, a);
