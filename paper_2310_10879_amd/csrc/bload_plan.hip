@@ -321,6 +321,114 @@ __global__ __launch_bounds__(kThreads) void plan_assign_kernel(
     }
 }
 
+// The whole plan of at most kTile sequences in one workgroup: the same steps
+// as the kernels above with the prefix sums, jump tables and head marks in LDS
+// and a barrier where the large path has a kernel boundary.
+__global__ __launch_bounds__(kThreads) void plan_small_kernel(
+    const int32_t* __restrict__ lengths, int32_t n_seq, int32_t t_blk, OrderKey key, int rounds,
+    int32_t* __restrict__ order, int32_t* __restrict__ block_of_seq,
+    int32_t* __restrict__ offset_of_seq, int32_t* __restrict__ block_first,
+    PlanResult* __restrict__ result)
+{
+    __shared__ int64_t s_prefix[kTile + 1];
+    __shared__ int32_t s_jump[2][kTile];
+    __shared__ uint8_t s_mark[kTile];
+    const int base = (int)threadIdx.x * kItems;
+
+    int32_t ord[kItems], len[kItems];
+    int64_t sum = 0;
+    int bad = 0;
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+        const int p = base + j;
+        ord[j] = 0;
+        len[j] = 0;
+        if (p < n_seq) {
+            ord[j] = order_at((uint32_t)p, (uint32_t)n_seq, key);
+            len[j] = lengths[ord[j]];
+            order[p] = ord[j];
+            bad |= (len[j] < 1) | (len[j] > t_blk);
+            sum += len[j];
+        }
+    }
+    int64_t total;
+    int64_t run = block_exclusive_scan<int64_t>(sum, 0, SumI64(), &total);
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+        if (base + j < n_seq) s_prefix[base + j] = run;
+        run += len[j];
+    }
+    if (threadIdx.x == 0) s_prefix[n_seq] = total;
+    bad = __syncthreads_or(bad);
+
+    // next[p]: the position that opens the next block if p opens one
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+        const int p = base + j;
+        if (p < n_seq) {
+            const int64_t limit = s_prefix[p] + t_blk;
+            int lo = p + 2, hi = (int)min((int64_t)n_seq, (int64_t)p + 1 + t_blk) + 1;
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (s_prefix[mid] > limit) hi = mid; else lo = mid + 1;
+            }
+            s_jump[0][p] = (lo <= n_seq) ? lo - 1 : n_seq;
+            s_mark[p] = (uint8_t)(p == 0);
+        }
+    }
+    // pointer jumping
+    int cur = 0;
+    for (int r = 0; r < rounds; ++r) {
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < kItems; ++j) {
+            const int p = base + j;
+            if (p < n_seq) {
+                const int32_t to = s_jump[cur][p];
+                if (to < n_seq) {
+                    if (s_mark[p]) s_mark[to] = 1;
+                    s_jump[cur ^ 1][p] = s_jump[cur][to];
+                } else {
+                    s_jump[cur ^ 1][p] = n_seq;
+                }
+            }
+        }
+        cur ^= 1;
+    }
+    __syncthreads();
+
+    // blocks, offsets, first positions
+    uint8_t m[kItems];
+    HeadPair v{0, -1};
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+        m[j] = (base + j < n_seq) ? s_mark[base + j] : (uint8_t)0;
+        if (m[j]) { v.cnt += 1; v.head = base + j; }
+    }
+    HeadPair all;
+    HeadPair at = block_exclusive_scan<HeadPair>(v, HeadPair{0, -1}, HeadOp(), &all);
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+        const int p = base + j;
+        if (p < n_seq) {
+            if (m[j]) {
+                at.cnt += 1;
+                at.head = p;
+                block_first[at.cnt - 1] = p;
+            }
+            block_of_seq[ord[j]] = at.cnt - 1;
+            offset_of_seq[ord[j]] = (int32_t)(s_prefix[p] - s_prefix[at.head]);
+            if (p == n_seq - 1) {
+                block_first[at.cnt] = n_seq;
+                result->num_blocks = at.cnt;
+                result->total_frames = total;
+                result->bad_length = bad;
+                result->pad_ = 0;
+            }
+        }
+    }
+}
+
 __global__ void plan_clear_result_kernel(PlanResult* result)
 {
     result->num_blocks = 0;
@@ -404,24 +512,32 @@ extern "C" bload_status bload_plan(const int32_t* d_lengths, int64_t n_seq, int3
     const dim3 tiles((uint32_t)l.n_tiles);
     const dim3 per_item((uint32_t)ceil_div(n_seq, kThreads));
 
-    hipLaunchKernelGGL(plan_clear_result_kernel, dim3(1), dim3(1), 0, stream, result);
-    hipLaunchKernelGGL(plan_order_kernel, tiles, block, 0, stream, d_lengths, n, t_blk, key, d_order,
-                       shuffled_len, tile_sum, result);
-    hipLaunchKernelGGL(plan_scan_tile_sums_kernel, dim3(1), block, 0, stream, tile_sum, l.n_tiles);
-    hipLaunchKernelGGL(plan_prefix_kernel, tiles, block, 0, stream, shuffled_len, n, tile_sum, prefix);
-    hipLaunchKernelGGL(plan_next_kernel, per_item, block, 0, stream, prefix, n, t_blk, jump_a, mark);
     // 2^rounds >= n_seq >= number of heads
     int rounds = 0;
     while (((int64_t)1 << rounds) < n_seq) ++rounds;
-    for (int r = 0; r < rounds; ++r) {
-        hipLaunchKernelGGL(plan_jump_kernel, per_item, block, 0, stream, jump_a, jump_b, mark, n);
-        int32_t* t = jump_a; jump_a = jump_b; jump_b = t;
+    if (n_seq <= kTile) {
+        hipLaunchKernelGGL(plan_small_kernel, dim3(1), block, 0, stream, d_lengths, n, t_blk, key,
+                           rounds, d_order, d_block_of_seq, d_offset_of_seq, d_block_first, result);
+    } else {
+        hipLaunchKernelGGL(plan_clear_result_kernel, dim3(1), dim3(1), 0, stream, result);
+        hipLaunchKernelGGL(plan_order_kernel, tiles, block, 0, stream, d_lengths, n, t_blk, key,
+                           d_order, shuffled_len, tile_sum, result);
+        hipLaunchKernelGGL(plan_scan_tile_sums_kernel, dim3(1), block, 0, stream, tile_sum, l.n_tiles);
+        hipLaunchKernelGGL(plan_prefix_kernel, tiles, block, 0, stream, shuffled_len, n, tile_sum,
+                           prefix);
+        hipLaunchKernelGGL(plan_next_kernel, per_item, block, 0, stream, prefix, n, t_blk, jump_a,
+                           mark);
+        for (int r = 0; r < rounds; ++r) {
+            hipLaunchKernelGGL(plan_jump_kernel, per_item, block, 0, stream, jump_a, jump_b, mark, n);
+            int32_t* t = jump_a; jump_a = jump_b; jump_b = t;
+        }
+        hipLaunchKernelGGL(plan_count_heads_kernel, tiles, block, 0, stream, mark, n, tile_cnt,
+                           tile_head);
+        hipLaunchKernelGGL(plan_scan_tile_heads_kernel, dim3(1), block, 0, stream, tile_cnt, tile_head,
+                           l.n_tiles);
+        hipLaunchKernelGGL(plan_assign_kernel, tiles, block, 0, stream, mark, d_order, prefix, n,
+                           tile_cnt, tile_head, d_block_of_seq, d_offset_of_seq, d_block_first, result);
     }
-    hipLaunchKernelGGL(plan_count_heads_kernel, tiles, block, 0, stream, mark, n, tile_cnt, tile_head);
-    hipLaunchKernelGGL(plan_scan_tile_heads_kernel, dim3(1), block, 0, stream, tile_cnt, tile_head,
-                       l.n_tiles);
-    hipLaunchKernelGGL(plan_assign_kernel, tiles, block, 0, stream, mark, d_order, prefix, n, tile_cnt,
-                       tile_head, d_block_of_seq, d_offset_of_seq, d_block_first, result);
     if (launch_status() != BLOAD_OK) return BLOAD_EHIP;
 
     PlanResult host{};
