@@ -128,10 +128,10 @@ bload_status bload_plan(const int32_t* d_lengths, int64_t n_seq, int32_t t_blk, 
  *                     (all five outputs 16-byte aligned)
  *
  * d_workspace         device scratch of >= bload_pack_workspace_bytes(...) bytes,
- *                     16-byte aligned (one int32 per 4 KiB of packed tensor when
- *                     frame_bytes >= 512: where each destination tile starts in
- *                     the shuffled order; 0 bytes for smaller frames, then the
- *                     pointer may be NULL); contents meaningless afterwards
+ *                     16-byte aligned (one int32 per destination tile -- 4 KiB of
+ *                     packed tensor when frame_bytes >= 512, else 1024 slots --
+ *                     saying where the tile starts in the shuffled order);
+ *                     contents meaningless afterwards
  *
  * Every byte of the five outputs is written exactly once (no prior memset is
  * needed).  Asynchronous on `hip_stream`.  n_seq = 0 / num_blocks = 0: no-op.

@@ -51,90 +51,53 @@ struct RunTable {
     int32_t n;
 };
 
-// Fill `tab` with the runs overlapping global slots [gs_lo, gs_hi).  Called by
-// one whole wave; the caller puts a barrier after it.
-//
-// Runs are sorted by destination in shuffled order, so the first overlapping
-// run is found by a 64-way search over the positions of the tile's first
-// block, then the table is read forward 64 positions at a time.
+// Fill `tab` with the runs that can overlap global slots [gs_lo, gs_hi), reading
+// the shuffled order forward from position `first` (the tile's entry of the
+// locate pass: the last position of the tile's first block that starts at or
+// before gs_lo).  Called by the whole workgroup, one candidate position per
+// participating thread and step; runs are sorted by destination, so the runs to keep are a
+// prefix of the candidates and candidate k becomes table entry k.  Ends with
+// a barrier.
 template <int MAXRUNS>
-__device__ __forceinline__ void find_runs(const PackArgs& a, int64_t gs_lo, int64_t gs_hi,
-                                          RunTable<MAXRUNS>& tab)
+__device__ __forceinline__ void gather_runs(const PackArgs& a, int32_t first, int64_t gs_lo,
+                                            int64_t gs_hi, RunTable<MAXRUNS>& tab)
 {
-    const int lane = lane_id();
+    const int tid = (int)threadIdx.x;
     const int32_t n_seq = a.n_seq;
-    const int64_t t_blk = a.t_blk;
-    const int64_t b0 = gs_lo / t_blk;
-    const int32_t rel = (int32_t)(gs_lo - b0 * t_blk);       // slot inside block b0
-
-    int32_t lo = min(max(a.block_first[b0], 0), n_seq);
-    int32_t hi = min(max(a.block_first[b0 + 1], lo), n_seq);
-    // A = first position p in [lo, hi) whose sequence ends after slot `rel` of
-    // block b0 (ends grow with p); hi if there is none.
-    while (hi - lo > kWave) {
-        const int32_t step = (hi - lo + kWave - 1) / kWave;
-        const int32_t q = lo + lane * step;
-        bool ends_after = true;
-        if (q < hi) {
-            const uint32_t i = (uint32_t)a.order[q];
-            ends_after = i >= (uint32_t)n_seq ||
-                         (int64_t)a.offset_of_seq[i] + a.lengths[i] > rel;
-        }
-        const uint64_t vote = __ballot(ends_after);
-        const int first = vote ? __ffsll((unsigned long long)vote) - 1 : kWave;
-        if (first == 0) { hi = lo; break; }
-        const int32_t probe_hit = lo + first * step;             // only meaningful if first < 64
-        lo = lo + (first - 1) * step + 1;
-        if (first < kWave && probe_hit < hi) hi = probe_hit;
-    }
-    {
-        const int32_t q = lo + lane;
-        bool ends_after = true;
-        if (q < hi) {
-            const uint32_t i = (uint32_t)a.order[q];
-            ends_after = i >= (uint32_t)n_seq ||
-                         (int64_t)a.offset_of_seq[i] + a.lengths[i] > rel;
-        }
-        const uint64_t vote = __ballot(ends_after);
-        lo += vote ? __ffsll((unsigned long long)vote) - 1 : kWave;
-    }
-
-    int n = 0;
-    for (int32_t base = lo; base < n_seq && n < MAXRUNS; base += kWave) {
-        const int32_t q = base + lane;
+    if (tid == 0) tab.n = INT_MAX;
+    __syncthreads();
+    // most tiles meet a handful of runs: look at 8 candidates first, then at 64,
+    // then at 256 per step, so that the table lookups stay in proportion
+    int32_t base = 0;
+    for (int32_t width = 8; base < MAXRUNS; base += width, width = width == 8 ? kWave : kThreads) {
+        const int32_t k = base + tid;
+        const int64_t q = (int64_t)first + k;
         bool take = false;
-        int64_t src = 0;
-        int32_t dst = 0, len = 0, seq = 0;
-        if (q < n_seq) {
+        if (tid < width && q < n_seq && k < MAXRUNS) {
             const uint32_t i = (uint32_t)a.order[q];
             if (i < (uint32_t)n_seq) {
-                const int64_t g = (int64_t)a.block_of_seq[i] * t_blk + a.offset_of_seq[i];
+                const int64_t g = (int64_t)a.block_of_seq[i] * a.t_blk + a.offset_of_seq[i];
                 take = g < gs_hi;
                 if (take) {
-                    dst = (int32_t)(g - gs_lo);
-                    len = a.lengths[i];
-                    seq = (int32_t)i;
-                    src = a.src_offsets[i];
+                    tab.src[k] = a.src_offsets[i];
+                    tab.dst[k] = (int32_t)(g - gs_lo);
+                    tab.len[k] = a.lengths[i];
+                    tab.seq[k] = (int32_t)i;
                 }
             }
         }
-        // runs are sorted by destination: the takers are the leading lanes
-        const uint64_t refuse = ~__ballot(take);
-        const int cnt = refuse ? __ffsll((unsigned long long)refuse) - 1 : kWave;
-        if (lane < cnt && n + lane < MAXRUNS) {
-            tab.src[n + lane] = src;
-            tab.dst[n + lane] = dst;
-            tab.len[n + lane] = len;
-            tab.seq[n + lane] = seq;
-        }
-        n += cnt;
-        if (cnt < kWave) break;
+        // the first candidate that is not kept ends the table
+        const uint64_t refuse = __ballot(tid < width && !take);
+        if (refuse && lane_id() == __ffsll((unsigned long long)refuse) - 1) atomicMin(&tab.n, k);
+        __syncthreads();
+        if (tab.n != INT_MAX) break;
     }
-    n = min(n, MAXRUNS);
-    if (lane == 0) {
+    if (tid == 0) {
+        const int32_t n = min(tab.n, MAXRUNS);
         tab.n = n;
         tab.dst[n] = INT_MAX;
     }
+    __syncthreads();
 }
 
 // Index of the last run whose first slot is <= slot (tile relative), -1 if none.
@@ -238,10 +201,11 @@ __device__ __forceinline__ void write_slots(const PackArgs& a, int64_t lo, int64
     }
 }
 
-// Pass 1: for every tile, the last shuffled position of the tile's first block
+// Pass 1 (used by both tile shapes, which come after it in this file's launch
+// order): for every tile, the last shuffled position of the tile's first block
 // whose sequence starts at or before the tile's first slot (the block's first
 // sequence starts at slot 0, so there is one).  One thread per tile.
-__global__ __launch_bounds__(kThreads) void pack_wide_locate_kernel(
+__global__ __launch_bounds__(kThreads) void pack_locate_kernel(
     const int32_t* __restrict__ order, const int32_t* __restrict__ offset_of_seq,
     const int32_t* __restrict__ block_first, int32_t n_seq, int64_t t_blk, int64_t frame_bytes,
     int64_t n_tiles, int32_t tile_bytes, double inv_frame_bytes, double inv_t_blk,
@@ -392,8 +356,12 @@ struct RunCursor {
     }
 };
 
-template <typename E>
-__global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a)
+// FUSED (4-byte frames, e.g. tokens): the four slots of a lane's start-table
+// quad are also exactly one 16-byte vector of payload, so both are written in
+// the same pass and the payload pass is skipped.
+template <typename E, bool FUSED>
+__global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a,
+                                                               const int32_t* __restrict__ first_pos)
 {
     __shared__ RunTable<kNarrowMaxRuns> tab;
     const int tid = (int)threadIdx.x;
@@ -401,8 +369,7 @@ __global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a)
     const int64_t g1 = min(g0 + kNarrowSlots, a.total_slots);
     const int nslot = (int)(g1 - g0);
 
-    if (wave_id() == 0) find_runs(a, g0, g1, tab);
-    __syncthreads();
+    gather_runs(a, min(max(first_pos[blockIdx.x], 0), a.n_seq), g0, g1, tab);
     const int n = tab.n;
 
     // start table: 4 consecutive slots per lane -> 16-byte / 4-byte stores
@@ -410,10 +377,27 @@ __global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a)
         const int32_t s0 = 4 * q;
         RunCursor<kNarrowMaxRuns> cur(tab, n, s0);
         int32_t sid[4], fid[4];
+        int64_t from[4];                 // source frame of each slot (FUSED only)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             fid[j] = (s0 + j < nslot) ? cur.seek(s0 + j) : -1;
             sid[j] = fid[j] >= 0 ? cur.seq : -1;
+            from[j] = cur.src + fid[j];
+        }
+        if (FUSED && s0 + 4 <= nslot) {
+            const uint32_t* src32 = reinterpret_cast<const uint32_t*>(a.src);
+            vec16 pv = {0u, 0u, 0u, 0u};
+            if (fid[0] >= 0 && sid[3] == sid[0] && fid[3] == fid[0] + 3) {
+                // one run: 16 contiguous source bytes (4-byte aligned)
+                typedef vec16 __attribute__((aligned(4))) vec16_a4;
+                pv = __builtin_nontemporal_load(reinterpret_cast<const vec16_a4*>(src32 + from[0]));
+            } else {
+                if (fid[0] >= 0) pv.x = src32[from[0]];
+                if (fid[1] >= 0) pv.y = src32[from[1]];
+                if (fid[2] >= 0) pv.z = src32[from[2]];
+                if (fid[3] >= 0) pv.w = src32[from[3]];
+            }
+            store_stream(reinterpret_cast<vec16*>(a.packed + (g0 + s0) * 4), pv);
         }
         const int64_t g = g0 + s0;
         if (s0 + 4 <= nslot) {
@@ -442,12 +426,13 @@ __global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a)
     // payload: one 16-byte destination vector per lane and step, assembled
     // from elements of type E (k elements per frame)
     constexpr int EPV = 16 / (int)sizeof(E);
+    const int done_slots = FUSED ? (nslot & ~3) : 0;            // already written above
     const int32_t k = (int32_t)(a.frame_bytes / (int64_t)sizeof(E));
     const int32_t tile_elems = nslot * k;                       // < 1024 * 512
     const int32_t nvec = (tile_elems + EPV - 1) / EPV;
     const E* src = reinterpret_cast<const E*>(a.src);
     uint8_t* dst_tile = a.packed + g0 * a.frame_bytes;          // 16-byte aligned
-    for (int32_t v = tid; v < nvec; v += kThreads) {
+    for (int32_t v = (FUSED ? done_slots / 4 : 0) + tid; v < nvec; v += kThreads) {
         const int32_t w = v * EPV;
         int32_t slot = w / k;
         int32_t j = w - slot * k;
@@ -478,10 +463,13 @@ using namespace bload;
 
 extern "C" size_t bload_pack_workspace_bytes(int64_t num_blocks, int32_t t_blk, int64_t frame_bytes)
 {
-    if (num_blocks <= 0 || t_blk < 1 || frame_bytes < kWideMinFrame) return 0;
+    if (num_blocks <= 0 || t_blk < 1 || frame_bytes < 1) return 0;
     const int64_t total_slots = num_blocks * (int64_t)t_blk;
     if (total_slots >= ((int64_t)1 << 40) || total_slots > (((int64_t)1 << 52) - 1) / frame_bytes) return 0;
-    return round_up((size_t)ceil_div(total_slots * frame_bytes, kWideTile) * sizeof(int32_t), 16);
+    // one int32 per tile: 4 KiB of packed tensor (wide frames) or 1024 slots (narrow frames)
+    const int64_t tiles = frame_bytes >= kWideMinFrame ? ceil_div(total_slots * frame_bytes, kWideTile)
+                                                       : ceil_div(total_slots, kNarrowSlots);
+    return round_up((size_t)tiles * sizeof(int32_t), 16);
 }
 
 extern "C" bload_status bload_pack(const void* d_src, const int64_t* d_src_offsets,
@@ -530,36 +518,37 @@ extern "C" bload_status bload_pack(const void* d_src, const int64_t* d_src_offse
     a.valid = d_valid;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
-    if (frame_bytes >= kWideMinFrame) {
-        const int64_t total_bytes = total_slots * frame_bytes;
-        if (total_bytes >= ((int64_t)1 << 52)) return BLOAD_EOVERFLOW;
-        const int32_t tile_bytes = kWideTile;
-        const int64_t tiles = ceil_div(total_bytes, tile_bytes);
-        if (tiles > INT32_MAX) return BLOAD_EOVERFLOW;
-        if (!d_workspace) return BLOAD_EINVAL;
-        if (!aligned_to(d_workspace, 16)) return BLOAD_EALIGN;
-        if (workspace_bytes < (size_t)tiles * sizeof(int32_t)) return BLOAD_EWORKSPACE;
-        int32_t* first_pos = static_cast<int32_t*>(d_workspace);
-        const double inv_frame = 1.0 / (double)frame_bytes, inv_t = 1.0 / (double)t_blk;
-        hipLaunchKernelGGL(pack_wide_locate_kernel, dim3((uint32_t)ceil_div(tiles, kThreads)),
-                           dim3(kThreads), 0, stream, d_order, d_offset_of_seq, d_block_first,
-                           (int32_t)n_seq, (int64_t)t_blk, frame_bytes, tiles, tile_bytes, inv_frame,
-                           inv_t, first_pos);
-        hipLaunchKernelGGL(pack_wide_kernel, dim3((uint32_t)tiles), dim3(kThreads), 0, stream, a,
-                           d_src_offsets, d_lengths, d_order, d_block_of_seq, d_offset_of_seq,
-                           first_pos, tile_bytes, inv_frame);
+    // pass 1 (both tile shapes): where each tile starts in the shuffled order.  The
+    // narrow tiles are 1024 slots, which the kernel takes as "1024 bytes of 1-byte frames".
+    const bool wide = frame_bytes >= kWideMinFrame;
+    const int64_t total_bytes = total_slots * frame_bytes;
+    if (total_bytes >= ((int64_t)1 << 52)) return BLOAD_EOVERFLOW;
+    const int64_t tiles = wide ? ceil_div(total_bytes, kWideTile) : ceil_div(total_slots, kNarrowSlots);
+    if (tiles > INT32_MAX) return BLOAD_EOVERFLOW;
+    if (!d_workspace) return BLOAD_EINVAL;
+    if (!aligned_to(d_workspace, 16)) return BLOAD_EALIGN;
+    if (workspace_bytes < (size_t)tiles * sizeof(int32_t)) return BLOAD_EWORKSPACE;
+    int32_t* first_pos = static_cast<int32_t*>(d_workspace);
+    const int64_t unit_bytes = wide ? frame_bytes : 1;
+    const int32_t tile_units = wide ? kWideTile : kNarrowSlots;
+    const double inv_unit = 1.0 / (double)unit_bytes, inv_t = 1.0 / (double)t_blk;
+    hipLaunchKernelGGL(pack_locate_kernel, dim3((uint32_t)ceil_div(tiles, kThreads)), dim3(kThreads), 0,
+                       stream, d_order, d_offset_of_seq, d_block_first, (int32_t)n_seq, (int64_t)t_blk,
+                       unit_bytes, tiles, tile_units, inv_unit, inv_t, first_pos);
+    const dim3 grid((uint32_t)tiles), block(kThreads);
+    if (wide) {
+        hipLaunchKernelGGL(pack_wide_kernel, grid, block, 0, stream, a, d_src_offsets, d_lengths,
+                           d_order, d_block_of_seq, d_offset_of_seq, first_pos, kWideTile, inv_unit);
+    } else if (frame_bytes % 16 == 0 && aligned_to(d_src, 16)) {
+        hipLaunchKernelGGL((pack_narrow_kernel<vec16, false>), grid, block, 0, stream, a, first_pos);
+    } else if (frame_bytes == 4 && aligned_to(d_src, 4)) {
+        hipLaunchKernelGGL((pack_narrow_kernel<uint32_t, true>), grid, block, 0, stream, a, first_pos);
+    } else if (frame_bytes % 4 == 0 && aligned_to(d_src, 4)) {
+        hipLaunchKernelGGL((pack_narrow_kernel<uint32_t, false>), grid, block, 0, stream, a, first_pos);
+    } else if (frame_bytes % 2 == 0 && aligned_to(d_src, 2)) {
+        hipLaunchKernelGGL((pack_narrow_kernel<uint16_t, false>), grid, block, 0, stream, a, first_pos);
     } else {
-        const int64_t tiles = ceil_div(total_slots, kNarrowSlots);
-        if (tiles > INT32_MAX) return BLOAD_EOVERFLOW;
-        const dim3 grid((uint32_t)tiles), block(kThreads);
-        if (frame_bytes % 16 == 0 && aligned_to(d_src, 16))
-            hipLaunchKernelGGL(pack_narrow_kernel<vec16>, grid, block, 0, stream, a);
-        else if (frame_bytes % 4 == 0 && aligned_to(d_src, 4))
-            hipLaunchKernelGGL(pack_narrow_kernel<uint32_t>, grid, block, 0, stream, a);
-        else if (frame_bytes % 2 == 0 && aligned_to(d_src, 2))
-            hipLaunchKernelGGL(pack_narrow_kernel<uint16_t>, grid, block, 0, stream, a);
-        else
-            hipLaunchKernelGGL(pack_narrow_kernel<uint8_t>, grid, block, 0, stream, a);
+        hipLaunchKernelGGL((pack_narrow_kernel<uint8_t, false>), grid, block, 0, stream, a, first_pos);
     }
     return launch_status();
 }
