@@ -17,7 +17,7 @@
 //   wide   (a frame is >= 64 bytes): lanes across the features of a frame, each
 //          row of lanes walks one chunk of time serially with several loads in
 //          flight, restarting its accumulators at every start flag.
-//   narrow (small frames, e.g. one token): lanes across time, 16 consecutive
+//   narrow (small frames, e.g. one token): lanes across time, 8 consecutive
 //          slots per lane, segmented scan over the workgroup with the start
 //          flags as segment heads and a carry between lanes and waves.
 #include "bload_common.hpp"
@@ -307,8 +307,8 @@ __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
 
 // ----------------------------------------------------------------- narrow
 
-constexpr int kSlotsPerLane = 16;
-constexpr int kNarrowTile = kThreads * kSlotsPerLane;      // 4096 slots per workgroup
+constexpr int kSlotsPerLane = 8;
+constexpr int kNarrowTile = kThreads * kSlotsPerLane;      // 2048 slots per workgroup
 
 // Running state of a segmented sum: `any` = a segment break was seen.
 template <typename Acc>
@@ -359,15 +359,16 @@ __global__ __launch_bounds__(kThreads) void reduce_narrow_kernel(ReduceArgs a)
     Acc* head_part = static_cast<Acc*>(a.head_part);
     Acc* tail_part = static_cast<Acc*>(a.tail_part);
 
-    // flags of this lane's 16 slots: bit j of vmask = valid, of bmask = segment break
+    // flags of this lane's slots: bit j of vmask = valid, of bmask = segment break
     // (a break is a padding slot, a start flag, or the first slot of a block)
     uint32_t vmask = 0, bmask = 0;
     {
         uint8_t rs[kSlotsPerLane], vl[kSlotsPerLane];
         if (s0 + kSlotsPerLane <= S) {
-            union { vec16 v; uint8_t b[16]; } ur, uv;
-            ur.v = load_stream(reinterpret_cast<const vec16*>(a.reset + s0));
-            uv.v = load_stream(reinterpret_cast<const vec16*>(a.valid + s0));
+            typedef uint32_t flag_words __attribute__((ext_vector_type(kSlotsPerLane / 4)));
+            union { flag_words v; uint8_t b[kSlotsPerLane]; } ur, uv;
+            ur.v = __builtin_nontemporal_load(reinterpret_cast<const flag_words*>(a.reset + s0));
+            uv.v = __builtin_nontemporal_load(reinterpret_cast<const flag_words*>(a.valid + s0));
 #pragma unroll
             for (int j = 0; j < kSlotsPerLane; ++j) { rs[j] = ur.b[j]; vl[j] = uv.b[j]; }
         } else {
@@ -418,7 +419,7 @@ __global__ __launch_bounds__(kThreads) void reduce_narrow_kernel(ReduceArgs a)
         Acc x[kSlotsPerLane];
         if (vec_payload) {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
+            for (int k = 0; k < kSlotsPerLane / 4; ++k) {
                 union { vec16 v; ElemT e[4]; } u;
                 u.v = load_stream(reinterpret_cast<const vec16*>(a.packed + (s0 + 4 * k) * esize));
 #pragma unroll
