@@ -177,7 +177,7 @@ def main() -> int:
             "reduction_vs_pad_to_longest": pad_longest / max(1, pad_blocks),
         },
         "roofline": {
-            "kernel": "pack_wide_kernel" if F >= 256 else "pack_narrow_kernel",
+            "kernel": "pack_wide_kernel" if F >= 512 else "pack_narrow_kernel",
             "bound": "hbm",
             "achieved": pack_gbps,
             "peak": HBM_PEAK_GBPS,

@@ -1,0 +1,131 @@
+"""Condense rocprofv3 CSV output of `bench.py` runs into the short summaries kept under profiles/.
+
+    python -m paper_2310_10879_amd.profile_summary --workload 2 \
+        --trace  gpurun_out/prof/kt/kt_kernel_stats.csv \
+        --fetch  gpurun_out/prof/fetch/fetch_counter_collection.csv \
+        --write  gpurun_out/prof/write/write_counter_collection.csv \
+        --bench  gpurun_out/prof/kt.json
+
+The three rocprofv3 runs that produce those files (each a run of its own, from the
+repository root on the MI355X machine; `--calibrate-copy` adds a plain 1 GiB elementwise copy
+whose known size scales the two HBM counters):
+
+    rocprofv3 --kernel-trace --stats --output-format csv -d gpurun_out/prof/kt -o kt -- \
+        python3 bench.py --workload W --steps 10 --warmup 2 --no-cpu-baseline --calibrate-copy
+    rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d gpurun_out/prof/fetch -o fetch -- \
+        python3 bench.py --workload W --steps 3 --warmup 1 --no-cpu-baseline --calibrate-copy
+    rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d gpurun_out/prof/write -o write -- \
+        python3 bench.py --workload W --steps 3 --warmup 1 --no-cpu-baseline --calibrate-copy
+
+Writes profiles/bload_workloadW_kernel_trace.md, profiles/bload_pack_workloadW_hbm_counters.md
+and profiles/bload_pack_workloadW_hbm_traffic.json (read back by bench.py for `roofline.traffic`).
+"""
+from __future__ import annotations
+
+import argparse
+import collections
+import csv
+import hashlib
+import json
+import os
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CAL_KIB = 1048576.0          # the calibration copy reads 1 GiB and writes 1 GiB
+
+
+def short(name: str) -> str:
+    if "MulFunctor" in name:
+        return "torch mul (1 GiB calibration copy)"
+    if "at::native" in name:
+        return "torch " + name.split("<")[0].split("::")[-1]
+    return name.split("(")[0].replace("void ", "")
+
+
+def counter_means(path):
+    acc = collections.defaultdict(list)
+    with open(path) as f:
+        for r in csv.DictReader(f):
+            acc[(short(r["Kernel_Name"]), r["Counter_Name"])].append(float(r["Counter_Value"]))
+    return {k: (sum(v) / len(v), len(v)) for k, v in acc.items()}
+
+
+def main() -> None:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", type=int, required=True)
+    ap.add_argument("--trace", required=True)
+    ap.add_argument("--fetch", required=True)
+    ap.add_argument("--write", required=True)
+    ap.add_argument("--bench", required=True, help="the JSON line bench.py printed in the trace run")
+    args = ap.parse_args()
+    w = args.workload
+    with open(args.bench) as f:
+        bench = json.loads([ln for ln in f if ln.startswith("{")][-1])
+    cfg = bench["config"]["workload"]
+
+    # ---- kernel trace
+    lines = [f"# rocprofv3 kernel trace of bench.py, workload {cfg}", "",
+             "Command (MI355X box, repository root):", "",
+             "    rocprofv3 --kernel-trace --stats --output-format csv -d gpurun_out/prof/kt -o kt -- \\",
+             f"        python3 bench.py --workload {w} --steps 10 --warmup 2 --no-cpu-baseline --calibrate-copy",
+             "", "Summarised by `python -m paper_2310_10879_amd.profile_summary` from kt_kernel_stats.csv.", "",
+             "| kernel | calls | avg ns | min ns | max ns | % of GPU time |", "|---|---|---|---|---|---|"]
+    with open(args.trace) as f:
+        for r in csv.DictReader(f):
+            lines.append(f"| {short(r['Name'])} | {r['Calls']} | {float(r['AverageNs']):.0f} | {r['MinNs']} | "
+                         f"{r['MaxNs']} | {float(r['Percentage']):.2f} |")
+    ph = bench["phases_ms"]
+    lines += ["", f"bench.py's event timing in the same run (ms per call): plan {ph['plan']:.4f}, "
+              f"pack {ph['pack']:.4f}, segment_reduce {ph['segment_reduce']:.4f}; "
+              f"pack roofline: {bench['roofline']['achieved']:.0f} GB/s of algorithmic bytes = "
+              f"{100 * bench['roofline']['frac']:.1f} % of {bench['roofline']['peak']:.0f} GB/s."]
+    with open(os.path.join(ROOT, "profiles", f"bload_workload{w}_kernel_trace.md"), "w") as f:
+        f.write("\n".join(lines) + "\n")
+
+    # ---- HBM counters
+    fetch, write = counter_means(args.fetch), counter_means(args.write)
+    cal = "torch mul (1 GiB calibration copy)"
+    f_scale = CAL_KIB / fetch[(cal, "FETCH_SIZE")][0]
+    w_scale = CAL_KIB / write[(cal, "WRITE_SIZE")][0]
+    pack_kernel = "bload::" + bench["roofline"]["kernel"]
+    alg = bench["roofline"]["algorithmic_bytes_per_launch"]
+    rows = ["| kernel | FETCH_SIZE KiB (raw) | read GB (scaled) | WRITE_SIZE KiB (raw) | written GB (scaled) |",
+            "|---|---|---|---|---|"]
+    traffic = None
+    names = sorted({k[0] for k in fetch} | {k[0] for k in write})
+    for name in names:
+        if not (name.startswith("bload::") or name == cal):
+            continue
+        fr = fetch.get((name, "FETCH_SIZE"), (0.0, 0))[0]
+        wr = write.get((name, "WRITE_SIZE"), (0.0, 0))[0]
+        rd_b, wr_b = fr * f_scale * 1024, wr * w_scale * 1024
+        if rd_b + wr_b < 1e6:
+            continue
+        rows.append(f"| {name} | {fr:.1f} | {rd_b / 1e9:.4f} | {wr:.1f} | {wr_b / 1e9:.4f} |")
+        if name.startswith(pack_kernel):
+            traffic = rd_b + wr_b
+    out = [f"# rocprofv3 HBM counters of bench.py, workload {cfg}", "",
+           "Two counter passes, each a run of its own (MI355X box, repository root):", "",
+           "    rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d gpurun_out/prof/fetch -o fetch -- \\",
+           f"        python3 bench.py --workload {w} --steps 3 --warmup 1 --no-cpu-baseline --calibrate-copy",
+           "    rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d gpurun_out/prof/write -o write -- \\",
+           f"        python3 bench.py --workload {w} --steps 3 --warmup 1 --no-cpu-baseline --calibrate-copy",
+           "", "Mean per dispatch.  Scale factors from the calibration copy (known: 1048576 KiB read, 1048576 KiB",
+           f"written): FETCH_SIZE x {f_scale:.5f}, WRITE_SIZE x {w_scale:.5f}.", ""] + rows
+    if traffic is not None:
+        out += ["", f"{pack_kernel}: {traffic / 1e9:.4f} GB of HBM traffic per launch against {alg / 1e9:.4f} GB of "
+                f"algorithmic bytes ({100 * (traffic / alg - 1):+.2f} %)."]
+        src = os.path.join(ROOT, "paper_2310_10879_amd", "csrc", "bload_pack.hip")
+        with open(src, "rb") as f:
+            digest = hashlib.sha256(f.read()).hexdigest()
+        with open(os.path.join(ROOT, "profiles", f"bload_pack_workload{w}_hbm_traffic.json"), "w") as f:
+            json.dump({"workload": w, "kernel": pack_kernel, "hbm_bytes_per_launch": traffic,
+                       "algorithmic_bytes_per_launch": alg, "fetch_scale": f_scale, "write_scale": w_scale,
+                       "kernel_source_sha256": digest}, f, indent=1)
+            f.write("\n")
+    with open(os.path.join(ROOT, "profiles", f"bload_pack_workload{w}_hbm_counters.md"), "w") as f:
+        f.write("\n".join(out) + "\n")
+    print("\n".join(lines[-1:] + out[-1:]))
+
+
+if __name__ == "__main__":
+    main()
