@@ -18,8 +18,8 @@
 //          row of lanes walks one chunk of time serially with several loads in
 //          flight, restarting its accumulators at every start flag.
 //   narrow (small frames, e.g. one token): lanes across time, 8 consecutive
-//          slots per lane, segmented scan over the workgroup with the start
-//          flags as segment heads and a carry between lanes and waves.
+//          slots per lane, segmented scan over the workgroup with the segment
+//          breaks as heads and a carry between lanes and waves.
 #include "bload_common.hpp"
 
 #include <hip/hip_fp16.h>
@@ -49,6 +49,7 @@ struct ReduceArgs {
     int32_t feat_dim;
     int32_t n_seq;
     int32_t mean;            // 1: divide by the frame count
+    double inv_t_blk;        // 1.0 / t_blk
     void* out;               // [n_seq, feat_dim] float or int64
     // chunking
     int32_t chunk;           // slots per chunk
@@ -306,20 +307,28 @@ __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
 }
 
 // ----------------------------------------------------------------- narrow
+//
+// Lanes across time: a workgroup takes 2048 consecutive slots (a "tile", which
+// may span several blocks), a lane 8 consecutive slots.  From the flags every
+// lane builds two 8-bit masks: valid, and "break" (a slot that cannot continue
+// the segment of the slot before it: padding, a start flag, a block's first
+// slot, or a slot that follows padding).  Sums are a segmented scan with the
+// breaks as heads: inside the lane, across the wave with shuffles, across the
+// four waves through LDS.  Frame counts need no scan: a segment's frames are
+// consecutive, so its count is (end position - position of its break + 1).
 
 constexpr int kSlotsPerLane = 8;
 constexpr int kNarrowTile = kThreads * kSlotsPerLane;      // 2048 slots per workgroup
 
-// Running state of a segmented sum: `any` = a segment break was seen.
+// Running state of a segmented sum: `any` = a break was seen.
 template <typename Acc>
-struct SegState { Acc sum; int32_t cnt; int32_t any; };
+struct SegState { Acc sum; int32_t any; };
 
 template <typename Acc>
 __device__ __forceinline__ SegState<Acc> seg_combine(SegState<Acc> left, SegState<Acc> right)
 {
     SegState<Acc> r;
     r.sum = right.any ? right.sum : left.sum + right.sum;
-    r.cnt = right.any ? right.cnt : left.cnt + right.cnt;
     r.any = left.any | right.any;
     return r;
 }
@@ -332,166 +341,305 @@ __device__ __forceinline__ SegState<Acc> seg_shfl_up(SegState<Acc> s, int d)
 {
     SegState<Acc> r;
     r.sum = shfl_up_acc(s.sum, d);
-    r.cnt = __shfl_up(s.cnt, d, kWave);
     r.any = __shfl_up(s.any, d, kWave);
     return r;
 }
 
+// What a lane knows about its 8 slots after reading the flags.
+struct LaneSegments {
+    uint32_t vmask;        // bit j: slot j is valid
+    uint32_t bmask;        // bit j: slot j is a break
+    uint32_t ends;         // bit j: a segment ends at slot j
+    int32_t prev_start;    // tile-relative position of the last break before this lane, -1 if none
+    int32_t j_last;        // index of the tile's last slot in this lane (may lie outside 0..7)
+    bool tail_open;        // the tile's last slot is here and its segment goes on into the next tile
+};
+
+// Reads the flags of the lane's slots and of its neighbours and derives the
+// masks.  Called by every thread of the workgroup; contains one barrier.
+// s_wave_start: LDS scratch, one int per wave.
+__device__ __forceinline__ LaneSegments narrow_lane_segments(const ReduceArgs& a, int64_t g0, int64_t g1,
+                                                             int32_t* s_wave_start)
+{
+    constexpr int SPL = kSlotsPerLane;
+    const int tid = (int)threadIdx.x;
+    const int lane = lane_id(), wave = wave_id();
+    const int64_t S = a.total_slots;
+    const uint32_t T = (uint32_t)a.t_blk;
+    const int pos0 = tid * SPL;
+    const int64_t s0 = g0 + pos0;
+    const int64_t sn = s0 + SPL;                         // the slot after this lane's last one
+    LaneSegments r;
+
+    uint8_t before_valid = 0, after_valid = 0, after_reset = 0;
+    if (lane == 0 && s0 > 0 && s0 <= S) before_valid = a.valid[s0 - 1];
+    if (lane == kWave - 1 && sn < S) { after_valid = a.valid[sn]; after_reset = a.reset[sn]; }
+
+    uint32_t vmask = 0, rmask = 0;
+    if (sn <= S) {
+        typedef uint32_t flag_words __attribute__((ext_vector_type(SPL / 4)));
+        union { flag_words v; uint8_t b[SPL]; } ur, uv;
+        ur.v = __builtin_nontemporal_load(reinterpret_cast<const flag_words*>(a.reset + s0));
+        uv.v = __builtin_nontemporal_load(reinterpret_cast<const flag_words*>(a.valid + s0));
+#pragma unroll
+        for (int j = 0; j < SPL; ++j) {
+            vmask |= (uint32_t)(uv.b[j] != 0) << j;
+            rmask |= (uint32_t)(ur.b[j] != 0) << j;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < SPL; ++j) {
+            if (s0 + j < S) {
+                vmask |= (uint32_t)(a.valid[s0 + j] != 0) << j;
+                rmask |= (uint32_t)(a.reset[s0 + j] != 0) << j;
+            }
+        }
+    }
+    // first slots of blocks: slot index modulo T, from the tile's remainder (the
+    // quotient comes from a double reciprocal, fixed up exactly).  `gap` = slots
+    // from this lane's first one to the next block start.
+    uint32_t smask = 0;
+    uint32_t rem_next;                                   // (s0 + SPL) mod T
+    {
+        int64_t blk = (int64_t)((double)g0 * a.inv_t_blk);
+        if (blk * (int64_t)T > g0) --blk; else if ((blk + 1) * (int64_t)T <= g0) ++blk;
+        const uint32_t tile_rem = (uint32_t)(g0 - blk * (int64_t)T);
+        const uint32_t rem0 = (tile_rem + (uint32_t)pos0) % T;
+        uint32_t gap = rem0 == 0 ? 0u : T - rem0;
+        while (gap < (uint32_t)SPL) { smask |= 1u << gap; gap += T; }
+        rem_next = (rem0 + (uint32_t)SPL) % T;
+    }
+    // validity of the slot before this lane's first one
+    uint32_t prev_valid = __shfl_up((vmask >> (SPL - 1)) & 1u, 1, kWave);
+    if (lane == 0) prev_valid = (uint32_t)(before_valid != 0);
+    const uint32_t after_pad = ~((vmask << 1) | prev_valid);          // bit j: slot j-1 is not valid
+    const uint32_t bmask = (~vmask | rmask | smask | after_pad) & ((1u << SPL) - 1u);
+    // is the slot after this lane's last one a break
+    uint32_t next_first = __shfl_down(bmask & 1u, 1, kWave);
+    if (lane == kWave - 1) {
+        next_first = 1u;
+        if (sn < S && rem_next != 0)
+            next_first = (!after_valid || after_reset || !((vmask >> (SPL - 1)) & 1u)) ? 1u : 0u;
+    }
+    const uint32_t next_brk = (bmask >> 1) | (next_first << (SPL - 1));
+    r.vmask = vmask;
+    r.bmask = bmask;
+    r.ends = vmask & next_brk;
+    r.j_last = (int32_t)(g1 - 1 - s0);
+    r.tail_open = r.j_last >= 0 && r.j_last < SPL && ((vmask >> r.j_last) & 1u) &&
+                  !((next_brk >> r.j_last) & 1u);
+
+    // position of the last break before this lane: inside the wave by a vote,
+    // from the waves before through LDS
+    const int32_t own_last = bmask ? pos0 + (31 - __clz((int)bmask)) : -1;
+    const uint64_t any_lanes = __ballot(bmask != 0);
+    const uint64_t lower = any_lanes & ((1ull << lane) - 1ull);
+    const int32_t got = __shfl(own_last, lower ? 63 - __clzll((long long)lower) : 0, kWave);
+    r.prev_start = lower ? got : -1;
+    const int32_t wave_last = __shfl(own_last, any_lanes ? 63 - __clzll((long long)any_lanes) : 0, kWave);
+    if (lane == 0) s_wave_start[wave] = any_lanes ? wave_last : -1;
+    __syncthreads();
+    if (r.prev_start < 0) {
+        for (int w = wave - 1; w >= 0; --w) {
+            const int32_t st = s_wave_start[w];
+            if (st >= 0) { r.prev_start = st; break; }
+        }
+    }
+    return r;
+}
+
+// The lane's elements of feature d, 0 where the slot is not valid.
+template <typename ElemT, typename Acc>
+__device__ __forceinline__ void narrow_load(const ReduceArgs& a, int64_t s0, int d, uint32_t vmask,
+                                            Acc (&x)[kSlotsPerLane])
+{
+    constexpr int SPL = kSlotsPerLane;
+    const int64_t esize = (int64_t)sizeof(ElemT);
+    const int D = a.feat_dim;
+    if (D == 1 && sizeof(ElemT) == 4 && s0 + SPL <= a.total_slots) {
+#pragma unroll
+        for (int k = 0; k < SPL / 4; ++k) {
+            union { vec16 v; ElemT e[4]; } u;
+            u.v = load_stream(reinterpret_cast<const vec16*>(a.packed + (s0 + 4 * k) * esize));
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                x[4 * k + j] = ((vmask >> (4 * k + j)) & 1u) ? Elem<ElemT>::get(u.e[j]) : (Acc)0;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < SPL; ++j) {
+            x[j] = 0;
+            if ((vmask >> j) & 1u)
+                x[j] = Elem<ElemT>::get(*reinterpret_cast<const ElemT*>(
+                    a.packed + ((s0 + j) * D + d) * esize));
+        }
+    }
+}
+
+// Hand one finished piece on: to the output row of its sequence, or to the
+// partial buffers when the tile border cuts its segment.
+template <typename Acc>
+__device__ __forceinline__ void narrow_emit(const ReduceArgs& a, int64_t q, int d, int64_t slot,
+                                            bool is_end, bool started, Acc sum, int32_t cnt,
+                                            ChunkDesc* s_desc)
+{
+    typedef typename OutOf<Acc>::T Out;
+    const int D = a.feat_dim;
+    if (is_end && started) {
+        const int32_t seq = a.seq_id[slot];
+        if ((uint32_t)seq < (uint32_t)a.n_seq)
+            static_cast<Out*>(a.out)[(int64_t)seq * D + d] = finish<Acc>(sum, cnt, a.mean);
+    } else if (!started) {
+        // continues a segment of the previous tile; closed here or running through
+        if (a.head_part) static_cast<Acc*>(a.head_part)[q * D + d] = sum;
+        if (d == 0) {
+            s_desc->head_state = is_end ? kHeadClosed : kHeadThrough;
+            s_desc->cnt_head = cnt;
+        }
+    } else {
+        if (a.tail_part) static_cast<Acc*>(a.tail_part)[q * D + d] = sum;
+        if (d == 0) {
+            s_desc->cnt_tail = cnt;
+            s_desc->seq_tail = a.seq_id[slot];
+        }
+    }
+}
+
+// Floating-point sums: segmented scan (only additions of the segment's own
+// terms, so no cancellation against neighbouring segments).
 template <typename ElemT>
 __global__ __launch_bounds__(kThreads) void reduce_narrow_kernel(ReduceArgs a)
 {
     typedef typename Elem<ElemT>::Acc Acc;
-    typedef typename OutOf<Acc>::T Out;
-    __shared__ SegState<Acc> s_wave[kThreads / kWave];
-    __shared__ uint32_t s_first_brk[kThreads / kWave];
+    constexpr int NW = kThreads / kWave;
+    constexpr int SPL = kSlotsPerLane;
+    __shared__ Acc s_wave_sum[NW];         // sum behind the wave's last break (whole wave if none)
+    __shared__ int32_t s_wave_any[NW];     // the wave holds a break
+    __shared__ int32_t s_wave_start[NW];
     __shared__ ChunkDesc s_desc;
 
     const int tid = (int)threadIdx.x;
     const int lane = lane_id(), wave = wave_id();
-    const int64_t S = a.total_slots;
-    const int64_t T = a.t_blk;
     const int64_t q = blockIdx.x;
     const int64_t g0 = q * kNarrowTile;
-    const int64_t g1 = min(S, g0 + kNarrowTile);
-    const int64_t s0 = g0 + (int64_t)tid * kSlotsPerLane;
-    const int D = a.feat_dim;
-    Out* out = static_cast<Out*>(a.out);
-    Acc* head_part = static_cast<Acc*>(a.head_part);
-    Acc* tail_part = static_cast<Acc*>(a.tail_part);
-
-    // flags of this lane's slots: bit j of vmask = valid, of bmask = segment break
-    // (a break is a padding slot, a start flag, or the first slot of a block)
-    uint32_t vmask = 0, bmask = 0;
-    {
-        uint8_t rs[kSlotsPerLane], vl[kSlotsPerLane];
-        if (s0 + kSlotsPerLane <= S) {
-            typedef uint32_t flag_words __attribute__((ext_vector_type(kSlotsPerLane / 4)));
-            union { flag_words v; uint8_t b[kSlotsPerLane]; } ur, uv;
-            ur.v = __builtin_nontemporal_load(reinterpret_cast<const flag_words*>(a.reset + s0));
-            uv.v = __builtin_nontemporal_load(reinterpret_cast<const flag_words*>(a.valid + s0));
-#pragma unroll
-            for (int j = 0; j < kSlotsPerLane; ++j) { rs[j] = ur.b[j]; vl[j] = uv.b[j]; }
-        } else {
-#pragma unroll
-            for (int j = 0; j < kSlotsPerLane; ++j) {
-                const bool in = s0 + j < S;
-                rs[j] = in ? a.reset[s0 + j] : (uint8_t)0;
-                vl[j] = in ? a.valid[s0 + j] : (uint8_t)0;
-            }
-        }
-        int64_t rem = s0 % T;                       // slot inside its block
-#pragma unroll
-        for (int j = 0; j < kSlotsPerLane; ++j) {
-            const bool v = vl[j] != 0;
-            const bool brk = !v || rs[j] != 0 || rem == 0;
-            vmask |= (uint32_t)v << j;
-            bmask |= (uint32_t)brk << j;
-            if (++rem == T) rem = 0;
-        }
-    }
-    // does a segment end at slot j: it is valid and the next slot is a break
-    if (lane == 0) s_first_brk[wave] = bmask & 1u;
+    const int64_t g1 = min(a.total_slots, g0 + kNarrowTile);
+    const int pos0 = tid * SPL;
+    const int64_t s0 = g0 + pos0;
     if (tid == 0) s_desc = ChunkDesc{kHeadNone, 0, 0, -1};
-    __syncthreads();
-    uint32_t next_first = __shfl_down(bmask & 1u, 1, kWave);
-    if (lane == kWave - 1) {
-        if (wave + 1 < kThreads / kWave) {
-            next_first = s_first_brk[wave + 1];
-        } else {
-            // the slot after the tile: past the end or a block's first slot closes the segment
-            next_first = 1u;
-            if (g0 + kNarrowTile < S && (g0 + kNarrowTile) % T != 0)
-                next_first = (!a.valid[g0 + kNarrowTile] || a.reset[g0 + kNarrowTile]) ? 1u : 0u;
-        }
-    }
-    const uint32_t next_brk = (bmask >> 1) | (next_first << (kSlotsPerLane - 1));
-    const uint32_t ends = vmask & next_brk;
-    // the tile's last slot, if its segment goes on into the next tile
-    const bool owns_last = (g1 - 1 >= s0) && (g1 - 1 < s0 + kSlotsPerLane);
-    const int j_last = (int)(g1 - 1 - s0);
-    const bool tail_open = owns_last && ((vmask >> j_last) & 1u) && !((next_brk >> j_last) & 1u);
+    const LaneSegments seg = narrow_lane_segments(a, g0, g1, s_wave_start);
+    const uint32_t bmask = seg.bmask;
 
-    const int64_t esize = (int64_t)sizeof(ElemT);
-    const bool vec_payload = (D == 1) && (sizeof(ElemT) == 4) && (s0 + kSlotsPerLane <= S);
-
-    for (int d = 0; d < D; ++d) {
-        // this lane's elements of feature d
-        Acc x[kSlotsPerLane];
-        if (vec_payload) {
+    for (int d = 0; d < a.feat_dim; ++d) {
+        Acc incl[SPL];
+        narrow_load<ElemT, Acc>(a, s0, d, seg.vmask, incl);
+        Acc run = 0;
 #pragma unroll
-            for (int k = 0; k < kSlotsPerLane / 4; ++k) {
-                union { vec16 v; ElemT e[4]; } u;
-                u.v = load_stream(reinterpret_cast<const vec16*>(a.packed + (s0 + 4 * k) * esize));
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    x[4 * k + j] = ((vmask >> (4 * k + j)) & 1u) ? Elem<ElemT>::get(u.e[j]) : (Acc)0;
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < kSlotsPerLane; ++j) {
-                x[j] = 0;
-                if ((vmask >> j) & 1u)
-                    x[j] = Elem<ElemT>::get(*reinterpret_cast<const ElemT*>(
-                        a.packed + ((s0 + j) * D + d) * esize));
-            }
+        for (int j = 0; j < SPL; ++j) {
+            if ((bmask >> j) & 1u) run = 0;
+            run += incl[j];
+            incl[j] = run;
         }
-        // segmented running sums inside the lane
-        SegState<Acc> run{0, 0, 0};
-        Acc incl[kSlotsPerLane];
-        int32_t cincl[kSlotsPerLane];
-#pragma unroll
-        for (int j = 0; j < kSlotsPerLane; ++j) {
-            if ((bmask >> j) & 1u) { run.sum = 0; run.cnt = 0; run.any = 1; }
-            run.sum += x[j];
-            run.cnt += (int32_t)((vmask >> j) & 1u);
-            incl[j] = run.sum;
-            cincl[j] = run.cnt;
-        }
-        // carry from the lanes before this one: wave scan, then the waves before this one
-        SegState<Acc> scan = run;
+        // carry from the lanes before this one: wave scan, then the waves before
+        SegState<Acc> scan{run, bmask != 0 ? 1 : 0};
 #pragma unroll
         for (int dd = 1; dd < kWave; dd <<= 1) {
             const SegState<Acc> left = seg_shfl_up(scan, dd);
             if (lane >= dd) scan = seg_combine(left, scan);
         }
         SegState<Acc> carry = seg_shfl_up(scan, 1);
-        if (lane == 0) carry = SegState<Acc>{0, 0, 0};
-        __syncthreads();                            // s_wave from the previous feature is consumed
-        if (lane == kWave - 1) s_wave[wave] = scan;
+        if (lane == 0) carry = SegState<Acc>{0, 0};
+        if (d > 0) __syncthreads();                  // the previous feature's wave sums are consumed
+        if (lane == kWave - 1) { s_wave_sum[wave] = scan.sum; s_wave_any[wave] = scan.any; }
         __syncthreads();
-        SegState<Acc> before{0, 0, 0};
-        for (int w = 0; w < wave; ++w) before = seg_combine(before, s_wave[w]);
+        SegState<Acc> before{0, 0};
+        for (int w = 0; w < wave; ++w)
+            before = seg_combine(before, SegState<Acc>{s_wave_sum[w], s_wave_any[w]});
         carry = seg_combine(before, carry);
 
-        // emit the segments that end in this lane
-        const uint32_t first_brk_bit = bmask ? (uint32_t)(__ffs((int)bmask) - 1) : 32u;
+        // the segments that end in this lane (rare), and the open tail of the tile
+        if (seg.ends != 0 || seg.tail_open) {
 #pragma unroll
-        for (int j = 0; j < kSlotsPerLane; ++j) {
-            const bool is_end = (ends >> j) & 1u;
-            const bool is_tail = tail_open && j == j_last;
-            if (!is_end && !is_tail) continue;
-            const bool lane_started = (uint32_t)j >= first_brk_bit;     // a break at or before j in this lane
-            const Acc sum = lane_started ? incl[j] : carry.sum + incl[j];
-            const int32_t cnt = lane_started ? cincl[j] : carry.cnt + cincl[j];
-            const bool started = lane_started || carry.any;             // the segment began inside the tile
-            if (is_end && started) {
-                const int32_t seq = a.seq_id[s0 + j];
-                if ((uint32_t)seq < (uint32_t)a.n_seq)
-                    out[(int64_t)seq * D + d] = finish<Acc>(sum, cnt, a.mean);
-            } else if (!started) {
-                // continues a segment of the previous tile; closed here or running through
-                if (head_part) head_part[q * D + d] = sum;
-                if (d == 0) {
-                    s_desc.head_state = is_end ? kHeadClosed : kHeadThrough;
-                    s_desc.cnt_head = cnt;
-                }
-            } else {
-                if (tail_part) tail_part[q * D + d] = sum;
-                if (d == 0) {
-                    s_desc.cnt_tail = cnt;
-                    s_desc.seq_tail = a.seq_id[s0 + j];
-                }
+            for (int j = 0; j < SPL; ++j) {
+                const bool is_end = (seg.ends >> j) & 1u;
+                if (!is_end && !(seg.tail_open && j == seg.j_last)) continue;
+                const uint32_t upto = bmask & ((2u << j) - 1u);          // breaks at or before j
+                const Acc sum = upto ? incl[j] : carry.sum + incl[j];
+                const int32_t start = upto ? pos0 + (31 - __clz((int)upto)) : seg.prev_start;
+                const int32_t cnt = start >= 0 ? pos0 + j - start + 1 : pos0 + j + 1;
+                narrow_emit<Acc>(a, q, d, s0 + j, is_end, start >= 0, sum, cnt, &s_desc);
             }
+        }
+    }
+    __syncthreads();
+    if (tid == 0 && a.desc) a.desc[q] = s_desc;
+}
+
+// Integer sums are exact, so a segment's sum can be taken as a difference of
+// plain prefix sums: the common path is one unsegmented scan of the lanes'
+// totals, and only a lane in which a segment ends (rare when segments are long)
+// looks up the prefix in front of the segment's first slot: the exclusive prefix
+// of the lane that holds it plus the few elements before it, both kept in LDS.
+__global__ __launch_bounds__(kThreads) void reduce_narrow_int_kernel(ReduceArgs a)
+{
+    typedef long long Acc;
+    constexpr int NW = kThreads / kWave;
+    constexpr int SPL = kSlotsPerLane;
+    __shared__ Acc s_lane_excl[kThreads];  // prefix sum in front of each lane, inside its wave
+    __shared__ int32_t s_x[kNarrowTile];   // the tile's elements of the current feature, 0 where not valid
+    __shared__ Acc s_wave_total[NW];
+    __shared__ int32_t s_wave_start[NW];
+    __shared__ ChunkDesc s_desc;
+
+    const int tid = (int)threadIdx.x;
+    const int lane = lane_id(), wave = wave_id();
+    const int64_t q = blockIdx.x;
+    const int64_t g0 = q * kNarrowTile;
+    const int64_t g1 = min(a.total_slots, g0 + kNarrowTile);
+    const int pos0 = tid * SPL;
+    const int64_t s0 = g0 + pos0;
+    const int D = a.feat_dim;
+    if (tid == 0) s_desc = ChunkDesc{kHeadNone, 0, 0, -1};
+    const LaneSegments seg = narrow_lane_segments(a, g0, g1, s_wave_start);
+
+    for (int d = 0; d < D; ++d) {
+        Acc x[SPL];
+        narrow_load<int32_t, Acc>(a, s0, d, seg.vmask, x);
+        Acc total = 0;
+#pragma unroll
+        for (int j = 0; j < SPL; ++j) total += x[j];
+        Acc incl = total;
+#pragma unroll
+        for (int dd = 1; dd < kWave; dd <<= 1) {
+            const Acc left = shfl_up_acc(incl, dd);
+            if (lane >= dd) incl += left;
+        }
+        if (d > 0) __syncthreads();                  // the previous feature's prefixes are consumed
+#pragma unroll
+        for (int j = 0; j < SPL; ++j) s_x[pos0 + j] = (int32_t)x[j];
+        s_lane_excl[tid] = incl - total;
+        if (lane == kWave - 1) s_wave_total[wave] = incl;
+        __syncthreads();
+
+        // segments that end in this lane, and the open tail of the tile
+        uint32_t todo = seg.ends | (seg.tail_open ? 1u << seg.j_last : 0u);
+        while (todo) {
+            const int j = __ffs((int)todo) - 1;
+            todo &= todo - 1;
+            // prefix sum of the tile in front of tile-relative position p
+            auto prefix_before = [&](int32_t p) {
+                const int owner = min(p / SPL, kThreads - 1);
+                Acc sum = s_lane_excl[owner];
+                for (int w = 0; w < owner / kWave; ++w) sum += s_wave_total[w];
+                for (int i = owner * SPL; i < p; ++i) sum += s_x[i];
+                return sum;
+            };
+            const bool is_end = (seg.ends >> j) & 1u;
+            const uint32_t upto = seg.bmask & ((2u << j) - 1u);          // breaks at or before j
+            const int32_t start = upto ? pos0 + (31 - __clz((int)upto)) : seg.prev_start;
+            const Acc upto_end = prefix_before(pos0 + j + 1);
+            const Acc sum = start >= 0 ? upto_end - prefix_before(start) : upto_end;
+            const int32_t cnt = start >= 0 ? pos0 + j - start + 1 : pos0 + j + 1;
+            narrow_emit<Acc>(a, q, d, s0 + j, is_end, start >= 0, sum, cnt, &s_desc);
         }
     }
     __syncthreads();
@@ -501,13 +649,25 @@ __global__ __launch_bounds__(kThreads) void reduce_narrow_kernel(ReduceArgs a)
 // ----------------------------------------------------------------- stitch
 
 // Segments cut by chunk borders: tail piece + the head pieces of the following
-// chunks, added in time order.  One workgroup per (chunk, 256 features).
+// chunks, added in time order.  One thread per (chunk, feature): a workgroup
+// takes 256 features of one chunk, or, for frames of fewer than 256 features,
+// all features of `chunks_per_wg` consecutive chunks.
 template <typename Acc>
-__global__ __launch_bounds__(kThreads) void reduce_stitch_kernel(ReduceArgs a, int32_t feat_tiles)
+__global__ __launch_bounds__(kThreads) void reduce_stitch_kernel(ReduceArgs a, int32_t feat_tiles,
+                                                                 int32_t chunks_per_wg)
 {
     typedef typename OutOf<Acc>::T Out;
-    const int64_t q = (int64_t)blockIdx.x / feat_tiles;
-    const int64_t d = ((int64_t)blockIdx.x % feat_tiles) * kThreads + threadIdx.x;
+    int64_t q, d;
+    if (chunks_per_wg > 1) {
+        const int32_t r = (int32_t)threadIdx.x / a.feat_dim;
+        if (r >= chunks_per_wg) return;
+        q = (int64_t)blockIdx.x * chunks_per_wg + r;
+        d = (int32_t)threadIdx.x - r * a.feat_dim;
+        if (q >= a.total_chunks) return;
+    } else {
+        q = (int64_t)blockIdx.x / feat_tiles;
+        d = ((int64_t)blockIdx.x % feat_tiles) * kThreads + threadIdx.x;
+    }
     const ChunkDesc first = a.desc[q];
     if (first.cnt_tail <= 0 || d >= a.feat_dim) return;
     const Acc* head_part = static_cast<const Acc*>(a.head_part);
@@ -608,13 +768,20 @@ static void launch_reduce(const ReducePlan& p, const ReduceArgs& a, hipStream_t 
     if (p.wide) {
         launch_wide<ElemT>(p, a, stream);
     } else {
-        hipLaunchKernelGGL(reduce_narrow_kernel<ElemT>, dim3((uint32_t)p.total_chunks), dim3(kThreads),
-                           0, stream, a);
+        if (sizeof(ElemT) == 4 && sizeof(Acc) == 8)
+            hipLaunchKernelGGL(reduce_narrow_int_kernel, dim3((uint32_t)p.total_chunks), dim3(kThreads),
+                               0, stream, a);
+        else
+            hipLaunchKernelGGL(reduce_narrow_kernel<ElemT>, dim3((uint32_t)p.total_chunks),
+                               dim3(kThreads), 0, stream, a);
     }
     if (p.partials) {
         const int32_t feat_tiles = (int32_t)ceil_div(a.feat_dim, kThreads);
-        hipLaunchKernelGGL(reduce_stitch_kernel<Acc>, dim3((uint32_t)(p.total_chunks * feat_tiles)),
-                           dim3(kThreads), 0, stream, a, feat_tiles);
+        const int32_t chunks_per_wg = a.feat_dim >= kThreads ? 1 : kThreads / a.feat_dim;
+        const int64_t groups = chunks_per_wg > 1 ? ceil_div(p.total_chunks, chunks_per_wg)
+                                                 : p.total_chunks * feat_tiles;
+        hipLaunchKernelGGL(reduce_stitch_kernel<Acc>, dim3((uint32_t)groups), dim3(kThreads), 0, stream,
+                           a, feat_tiles, chunks_per_wg);
     }
 }
 
@@ -671,6 +838,7 @@ extern "C" bload_status bload_segment_reduce(const void* d_packed, const int32_t
     a.feat_dim = (int32_t)feat_dim;
     a.n_seq = (int32_t)n_seq;
     a.mean = op == BLOAD_MEAN ? 1 : 0;
+    a.inv_t_blk = 1.0 / (double)t_blk;
     a.out = d_out;
     a.chunk = p.chunk;
     a.n_chunks = p.n_chunks;
