@@ -61,7 +61,9 @@ def test_workspace_queries(lib):
     f = lib.bload_segment_reduce_workspace_bytes
     f.restype = ctypes.c_size_t
     f.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int64, ctypes.c_int]
-    assert f(324084, 4096, 1, 3) == 0              # token blocks end on tile borders
+    tiles = 324084 * 4096 // 2048                  # token segments can cross the 2048-slot tiles:
+    assert f(324084, 4096, 1, 3) == tiles * (16 + 8 + 8)   # a descriptor and two int64 partials each
+    assert f(5, 2048, 1, 3) == 0                   # tiles that are whole blocks cut nothing
     assert f(34576, 3000, 80, 2) == 0              # one chunk per block
     assert f(180, 600, 37632, 0) > 0               # video blocks are cut in time
     assert f(0, 600, 8, 0) == 0 and f(5, 0, 8, 0) == 0 and f(5, 8, 8, 7) == 0
