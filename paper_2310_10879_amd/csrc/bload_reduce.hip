@@ -404,10 +404,12 @@ __device__ __forceinline__ LaneSegments narrow_lane_segments(const ReduceArgs& a
         int64_t blk = (int64_t)((double)g0 * a.inv_t_blk);
         if (blk * (int64_t)T > g0) --blk; else if ((blk + 1) * (int64_t)T <= g0) ++blk;
         const uint32_t tile_rem = (uint32_t)(g0 - blk * (int64_t)T);
-        const uint32_t rem0 = (tile_rem + (uint32_t)pos0) % T;
+        uint32_t rem0 = tile_rem + (uint32_t)pos0;
+        if (rem0 >= T) rem0 %= T;
         uint32_t gap = rem0 == 0 ? 0u : T - rem0;
         while (gap < (uint32_t)SPL) { smask |= 1u << gap; gap += T; }
-        rem_next = (rem0 + (uint32_t)SPL) % T;
+        rem_next = rem0 + (uint32_t)SPL;
+        if (rem_next >= T) rem_next %= T;
     }
     // validity of the slot before this lane's first one
     uint32_t prev_valid = __shfl_up((vmask >> (SPL - 1)) & 1u, 1, kWave);
@@ -448,19 +450,37 @@ __device__ __forceinline__ LaneSegments narrow_lane_segments(const ReduceArgs& a
     return r;
 }
 
+// Single-feature frames of 4-byte elements: the lane's 8 elements are 32
+// contiguous bytes whose address does not depend on the flags, so they can be
+// requested before the flags are looked at.
+struct NarrowEarly { vec16 raw[kSlotsPerLane / 4]; bool used; };
+
+template <typename ElemT>
+__device__ __forceinline__ NarrowEarly narrow_load_early(const ReduceArgs& a, int64_t s0)
+{
+    NarrowEarly e;
+    e.used = a.feat_dim == 1 && sizeof(ElemT) == 4 && s0 + kSlotsPerLane <= a.total_slots;
+    if (e.used) {
+#pragma unroll
+        for (int k = 0; k < kSlotsPerLane / 4; ++k)
+            e.raw[k] = load_stream(reinterpret_cast<const vec16*>(a.packed + (s0 + 4 * k) * (int64_t)sizeof(ElemT)));
+    }
+    return e;
+}
+
 // The lane's elements of feature d, 0 where the slot is not valid.
 template <typename ElemT, typename Acc>
 __device__ __forceinline__ void narrow_load(const ReduceArgs& a, int64_t s0, int d, uint32_t vmask,
-                                            Acc (&x)[kSlotsPerLane])
+                                            const NarrowEarly& early, Acc (&x)[kSlotsPerLane])
 {
     constexpr int SPL = kSlotsPerLane;
     const int64_t esize = (int64_t)sizeof(ElemT);
     const int D = a.feat_dim;
-    if (D == 1 && sizeof(ElemT) == 4 && s0 + SPL <= a.total_slots) {
+    if (early.used) {
 #pragma unroll
         for (int k = 0; k < SPL / 4; ++k) {
             union { vec16 v; ElemT e[4]; } u;
-            u.v = load_stream(reinterpret_cast<const vec16*>(a.packed + (s0 + 4 * k) * esize));
+            u.v = early.raw[k];
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 x[4 * k + j] = ((vmask >> (4 * k + j)) & 1u) ? Elem<ElemT>::get(u.e[j]) : (Acc)0;
@@ -526,12 +546,13 @@ __global__ __launch_bounds__(kThreads) void reduce_narrow_kernel(ReduceArgs a)
     const int pos0 = tid * SPL;
     const int64_t s0 = g0 + pos0;
     if (tid == 0) s_desc = ChunkDesc{kHeadNone, 0, 0, -1};
+    const NarrowEarly early = narrow_load_early<ElemT>(a, s0);
     const LaneSegments seg = narrow_lane_segments(a, g0, g1, s_wave_start);
     const uint32_t bmask = seg.bmask;
 
     for (int d = 0; d < a.feat_dim; ++d) {
         Acc incl[SPL];
-        narrow_load<ElemT, Acc>(a, s0, d, seg.vmask, incl);
+        narrow_load<ElemT, Acc>(a, s0, d, seg.vmask, early, incl);
         Acc run = 0;
 #pragma unroll
         for (int j = 0; j < SPL; ++j) {
@@ -599,11 +620,12 @@ __global__ __launch_bounds__(kThreads) void reduce_narrow_int_kernel(ReduceArgs 
     const int64_t s0 = g0 + pos0;
     const int D = a.feat_dim;
     if (tid == 0) s_desc = ChunkDesc{kHeadNone, 0, 0, -1};
+    const NarrowEarly early = narrow_load_early<int32_t>(a, s0);
     const LaneSegments seg = narrow_lane_segments(a, g0, g1, s_wave_start);
 
     for (int d = 0; d < D; ++d) {
         Acc x[SPL];
-        narrow_load<int32_t, Acc>(a, s0, d, seg.vmask, x);
+        narrow_load<int32_t, Acc>(a, s0, d, seg.vmask, early, x);
         Acc total = 0;
 #pragma unroll
         for (int j = 0; j < SPL; ++j) total += x[j];
