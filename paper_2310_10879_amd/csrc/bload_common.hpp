@@ -54,4 +54,16 @@ __device__ __forceinline__ void store_stream(vec16* p, vec16 v)
     __builtin_nontemporal_store(v, p);
 }
 
+// The hardware deals consecutive workgroups round-robin to the 8 XCDs (each with
+// its own L2 and its own path to HBM).  This maps workgroup b of n to a work item
+// so that every XCD walks one contiguous eighth of the items: b -> (XCD b % 8,
+// step b / 8) -> first item of that XCD + step.  A bijection of [0, n) for any n.
+constexpr uint32_t kXcds = 8;
+__device__ __forceinline__ uint32_t xcd_contiguous(uint32_t b, uint32_t n)
+{
+    const uint32_t full = n / kXcds, rem = n % kXcds;
+    const uint32_t x = b % kXcds, y = b / kXcds;
+    return x * full + min(x, rem) + y;
+}
+
 }  // namespace bload

@@ -115,9 +115,10 @@ __device__ __forceinline__ int run_of_slot(const RunTable<MAXRUNS>& tab, int n, 
 // ------------------------------------------------------------------- wide
 //
 // One workgroup writes one small flat piece of the packed tensor and ends:
-// workgroups that run at the same time then touch one compact window of the
-// destination (and a handful of source streams), which is what HBM wants; a
-// workgroup that loops over a large private tile does measurably worse.
+// workgroups that run at the same time then touch a few compact windows of the
+// destination (one per XCD, see xcd_contiguous) and a handful of source
+// streams, which is what HBM wants; a workgroup that loops over a large private
+// tile does measurably worse.
 // To keep so short a workgroup cheap there is no LDS and no barrier here, and
 // the lookup of the tile's runs is wave-uniform (a binary search over the
 // block's positions followed by a walk over consecutive positions), so it
@@ -239,10 +240,11 @@ __global__ __launch_bounds__(kThreads) void pack_wide_kernel(
     const int64_t T = a.t_blk;
     const int32_t n_seq = a.n_seq;
     const int64_t total_bytes = a.total_slots * F;
-    const int64_t D0 = (int64_t)blockIdx.x * tile_bytes;
+    const uint32_t tile = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int64_t D0 = (int64_t)tile * tile_bytes;
     const int64_t D1 = min(D0 + (int64_t)tile_bytes, total_bytes);
     const bool table_wave = wave_id() == 0;
-    int32_t p = min(max(first_pos[blockIdx.x], 0), n_seq);
+    int32_t p = min(max(first_pos[tile], 0), n_seq);
 
     // the common case first: the tile lies inside one run -- one load and one
     // store per thread, plus the start-table entries of the few frames that
@@ -365,11 +367,12 @@ __global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a,
 {
     __shared__ RunTable<kNarrowMaxRuns> tab;
     const int tid = (int)threadIdx.x;
-    const int64_t g0 = (int64_t)blockIdx.x * kNarrowSlots;
+    const uint32_t tile = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int64_t g0 = (int64_t)tile * kNarrowSlots;
     const int64_t g1 = min(g0 + kNarrowSlots, a.total_slots);
     const int nslot = (int)(g1 - g0);
 
-    gather_runs(a, min(max(first_pos[blockIdx.x], 0), a.n_seq), g0, g1, tab);
+    gather_runs(a, min(max(first_pos[tile], 0), a.n_seq), g0, g1, tab);
     const int n = tab.n;
 
     // start table: 4 consecutive slots per lane -> 16-byte / 4-byte stores
