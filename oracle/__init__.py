@@ -58,6 +58,10 @@ def _load():
                                                     ctypes.c_void_p, ctypes.c_int64,
                                                     ctypes.c_int64, ctypes.c_int, ctypes.c_int,
                                                     ctypes.c_void_p]
+        lib.bload_oracle_plan_shard.restype = ctypes.c_int64
+        lib.bload_oracle_plan_shard.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_int64, ctypes.c_int64,
+                                                                       ctypes.c_int32, ctypes.c_int32] + \
+            [ctypes.c_void_p] * 3
         lib.bload_oracle_padding.restype = None
         lib.bload_oracle_padding.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
                                              ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
@@ -125,6 +129,26 @@ def plan(lengths, t_blk: int, order_) -> Plan:
     b = int(nb[0])
     return Plan(o, block_of, offset_of, block_first[:b + 1].copy() if n else block_first[:0],
                 b, int(tot[0]), t_blk)
+
+
+def plan_shard(pl: Plan, rank: int, world: int) -> Plan:
+    """Worker ``rank``'s share of the plan (blocks b = rank mod world, plus a padding block
+    when the worker would fall short): a Plan whose tables are local to the worker.
+    ``order`` keeps length N with -1 behind the worker's own sequences."""
+    n = pl.order.shape[0]
+    nb_local = -(-pl.num_blocks // world)
+    order_local = np.full(n, -7, dtype=np.int32)
+    block_of_local = np.full(n, -7, dtype=np.int32)
+    block_first_local = np.full(nb_local + 1, -7, dtype=np.int32)
+    bf = np.zeros(pl.num_blocks + 1, dtype=np.int32)
+    bf[:] = pl.block_first
+    n_local = _load().bload_oracle_plan_shard(_p(pl.order), _p(pl.block_of_seq), _p(bf), n,
+                                              pl.num_blocks, rank, world, _p(order_local),
+                                              _p(block_of_local), _p(block_first_local))
+    out = Plan(order_local, block_of_local, pl.offset_of_seq, block_first_local, nb_local,
+               pl.total_frames, pl.t_blk)
+    out.n_local = int(n_local)
+    return out
 
 
 def alloc_pack_outputs(nb: int, t_blk: int, frame_bytes: int):

@@ -262,3 +262,41 @@ void bload_oracle_padding(const int32_t* lengths, int64_t n, int64_t t_max,
     *pad_longest = n * t_max - total;
     *pad_blocks = num_blocks * t_blk - total;
 }
+
+/* ------------------------------------------------------------------ shard */
+
+/* The share of data-parallel worker `rank` of `world` (Problem Statement: every
+ * worker must get the same number of samples, or the gradient exchange stalls):
+ * the blocks b with b mod world == rank, renumbered j = b / world, and, for the
+ * workers that would otherwise fall one block short, one block of pure padding
+ * at the end, so that every worker holds ceil(B / world) blocks.
+ *   order_local[n]          visiting order of the worker's sequences, then -1
+ *   block_of_seq_local[n]   local block j of sequence i, -1 if i is another worker's
+ *   block_first_local[..]   ceil(B / world) + 1 entries
+ * Returns the number of sequences of the worker. */
+int64_t bload_oracle_plan_shard(const int32_t* order, const int32_t* block_of_seq,
+                                const int32_t* block_first, int64_t n, int64_t num_blocks,
+                                int32_t rank, int32_t world,
+                                int32_t* order_local, int32_t* block_of_seq_local,
+                                int32_t* block_first_local)
+{
+    int64_t blocks_local = (num_blocks + world - 1) / world;
+    int64_t n_local = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        order_local[i] = -1;
+        block_of_seq_local[i] = -1;
+    }
+    for (int64_t j = 0; j < blocks_local; ++j) {
+        int64_t b = j * world + rank;
+        block_first_local[j] = (int32_t)n_local;
+        if (b >= num_blocks) continue;                   /* the padding block */
+        for (int64_t p = block_first[b]; p < block_first[b + 1]; ++p) {
+            int32_t i = order[p];
+            (void)block_of_seq;
+            order_local[n_local++] = i;
+            block_of_seq_local[i] = (int32_t)j;
+        }
+    }
+    block_first_local[blocks_local] = (int32_t)n_local;
+    return n_local;
+}
