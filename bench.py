@@ -52,6 +52,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--world", type=int, default=1,
+                    help="time the share of one data-parallel worker (blocks rank mod world, "
+                         "bload_plan_shard) instead of the whole workload; still one GPU")
+    ap.add_argument("--rank", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise copy of 1 GiB (read 1 GiB, write 1 GiB) "
                          "three times before the steps, as the known-size kernel that the "
@@ -82,7 +86,15 @@ def main() -> int:
     # everything the steps write is allocated once, outside the timed region
     plan_ws = torch.empty(max(16, bload.bload_plan_workspace_bytes(N)), dtype=torch.uint8, device=dev)
     plan = bload.bload_plan(d_L, T, seed, workspace=plan_ws)
-    B = plan.num_blocks
+    sharded = args.world > 1
+    if sharded:
+        share = bload.bload_plan_shard(plan, args.rank, args.world)
+        mine = share.block_of_seq >= 0
+        local_frames = int(d_L[mine].sum().item())
+        local_seqs = int(mine.sum().item())
+    else:
+        share, local_frames, local_seqs = plan, total_frames, N
+    B = share.num_blocks
     packed = bload.alloc_packed(B, T, F, dev)
     pack_ws = torch.empty(max(16, bload.bload_pack_workspace_bytes(B, T, F)), dtype=torch.uint8,
                           device=dev)
@@ -96,13 +108,14 @@ def main() -> int:
         if events:
             events[0].record()
         bload.bload_plan(d_L, T, seed, workspace=plan_ws, out=plan)
+        todo = bload.bload_plan_shard(plan, args.rank, args.world) if sharded else plan
         if events:
             events[1].record()
-        bload.bload_pack(d_src, d_so, d_L, plan, F, out=packed, workspace=pack_ws)
+        bload.bload_pack(d_src, d_so, d_L, todo, F, out=packed, workspace=pack_ws)
         if events:
             events[2].record()
         bload.bload_segment_reduce(packed.packed, packed.seq_id, packed.reset, packed.valid,
-                                   plan.num_blocks, T, D, w.dtype, w.op, N, out=red,
+                                   todo.num_blocks, T, D, w.dtype, w.op, N, out=red,
                                    workspace=red_ws)
         if events:
             events[3].record()
@@ -123,7 +136,8 @@ def main() -> int:
         step(ev[k])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    assert plan.num_blocks == B and plan.total_frames == total_frames
+    assert share.num_blocks == B and plan.total_frames == total_frames
+    work_frames = local_frames              # valid frames one step packs
 
     ms = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in ev])   # plan, pack, reduce
     plan_ms, pack_ms, reduce_ms = (float(x) for x in ms.mean(axis=0))
@@ -131,17 +145,17 @@ def main() -> int:
 
     slots = B * T
     acc = 8 if w.dtype == "i32" else 4
-    bytes_pack = total_frames * F + slots * F + 10 * slots + 16 * N
+    bytes_pack = work_frames * F + slots * F + 10 * slots + 16 * local_seqs
     bytes_reduce = slots * (F + 6) + N * D * acc
     pack_gbps = bytes_pack / (pack_ms * 1e-3) / 1e9
-    pad_blocks = slots - total_frames
-    pad_longest = N * T - total_frames
+    pad_blocks = slots - work_frames
+    pad_longest = local_seqs * T - work_frames
     kernel_src = os.path.join(ROOT, "paper_2310_10879_amd", "csrc", "bload_pack.hip")
     traffic = measured_traffic(kernel_src, w.wid)
 
     result = {
         "metric": "packed_frames_per_s",
-        "value": total_frames * args.steps / elapsed,
+        "value": work_frames * args.steps / elapsed,
         "unit": "frames/s",
         "n_gpus": 1,
         "steps": args.steps,
@@ -153,14 +167,15 @@ def main() -> int:
         "dtype": w.dtype,
         "data": "synthetic",
         "config": {
-            "workload": f"{w.wid}: N={N} {w.name}, T_blk={T}, frame_bytes={F}, seed={seed}",
+            "workload": f"{w.wid}: N={N} {w.name}, T_blk={T}, frame_bytes={F}, seed={seed}"
+                        + (f", share of worker {args.rank} of {args.world}" if sharded else ""),
             "n_seq": N, "t_blk": T, "frame_bytes": F, "total_frames": total_frames,
             "num_blocks": B, "lengths": "lognormal(mu=ln 60, sigma=1) clipped to [1,600]"
             if w.wid == 2 else "see workloads.py",
         },
         "phases_ms": {"plan": plan_ms, "pack": pack_ms, "segment_reduce": reduce_ms},
         "pack": {
-            "frames_per_s": total_frames / (pack_ms * 1e-3),
+            "frames_per_s": work_frames / (pack_ms * 1e-3),
             "algorithmic_GBps": pack_gbps,
             "pct_of_hbm_peak": 100.0 * pack_gbps / HBM_PEAK_GBPS,
             "min_ms": float(ms[:, 1].min()), "median_ms": float(np.median(ms[:, 1])),
@@ -169,11 +184,11 @@ def main() -> int:
             "algorithmic_GBps": bytes_reduce / (reduce_ms * 1e-3) / 1e9,
         },
         "padding": {
-            "fill": total_frames / slots,
+            "fill": work_frames / slots,
             "pad_blocks_frames": pad_blocks,
             "pad_to_longest_frames": pad_longest,
             "pad_ratio_blocks": pad_blocks / slots,
-            "pad_ratio_to_longest": pad_longest / (N * T),
+            "pad_ratio_to_longest": pad_longest / (local_seqs * T),
             "reduction_vs_pad_to_longest": pad_longest / max(1, pad_blocks),
         },
         "roofline": {
@@ -189,7 +204,7 @@ def main() -> int:
         },
     }
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not sharded:
         import oracle
         # the oracle as it stands, one thread: order + plan + pack + reduce of the same workload
         out = oracle.alloc_pack_outputs(B, T, F)

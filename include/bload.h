@@ -104,6 +104,37 @@ bload_status bload_plan(const int32_t* d_lengths, int64_t n_seq, int32_t t_blk, 
                         int64_t* h_num_blocks, int64_t* h_total_frames,
                         void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ------------------------------------------------------------ plan shard --
+ * Problem Statement: under data-parallel training every worker must receive the
+ * same number of samples per epoch, otherwise the gradient exchange stalls; the
+ * blocks are the samples.  This call derives worker `rank`'s share of a plan:
+ * the blocks b with b mod world == rank, renumbered j = b / world, plus one
+ * block of pure padding at the end for the workers that would otherwise hold
+ * one block less, so that every worker has ceil(B / world) blocks.  The outputs
+ * are a plan in the worker's own numbering; bload_pack and bload_segment_reduce
+ * take them like the tables of bload_plan (with n_seq unchanged, the worker's
+ * block count, and the same d_lengths / d_offset_of_seq / d_src / d_src_offsets).
+ *
+ * d_order, d_block_of_seq, d_block_first   in   as produced by bload_plan
+ * d_order_local          out  int32[n_seq]  the worker's sequences in visiting
+ *                                           order, then -1 (= no sequence)
+ * d_block_of_seq_local   out  int32[n_seq]  local block of sequence i, -1 when i
+ *                                           belongs to another worker
+ * d_block_first_local    out  int32[ceil(B / world) + 1]
+ * h_num_blocks_local     out  host int64    ceil(B / world)
+ * h_n_seq_local          out  host int64    number of sequences of the worker
+ * d_workspace                 >= 16 bytes, 16-byte aligned
+ *
+ * Synchronises the stream before returning (it reports the worker's counts).
+ */
+bload_status bload_plan_shard(const int32_t* d_order, const int32_t* d_block_of_seq,
+                              const int32_t* d_block_first, int64_t n_seq, int64_t num_blocks,
+                              int32_t rank, int32_t world,
+                              int32_t* d_order_local, int32_t* d_block_of_seq_local,
+                              int32_t* d_block_first_local,
+                              int64_t* h_num_blocks_local, int64_t* h_n_seq_local,
+                              void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
 /* ------------------------------------------------------------------ pack --
  * Methods section: the sequences of a block are laid one after another and the
  * rest of the block is filled with 0's; the start table says where each new
@@ -116,7 +147,9 @@ bload_status bload_plan(const int32_t* d_lengths, int64_t n_seq, int32_t t_blk, 
  * d_src_offsets  in   int64[n_seq+1]  first source frame of each sequence;
  *                     src_offsets[i+1] - src_offsets[i] must equal L_i (not checked)
  * d_lengths, d_order, d_block_of_seq, d_offset_of_seq, d_block_first
- *                in   as produced by bload_plan for the same lengths
+ *                in   as produced by bload_plan for the same lengths (or a worker's
+ *                     share of them from bload_plan_shard; an entry of d_order that
+ *                     is not in [0, n_seq) ends the list of sequences)
  * num_blocks     in   B as returned by bload_plan
  * d_packed       out  bytes[B, t_blk, frame_bytes]; slot
  *                     (b, offset_of_seq[i] + t) receives frame t of sequence i,

@@ -42,6 +42,9 @@ _lib.bload_plan_workspace_bytes.argtypes = [_i64]
 _lib.bload_plan.restype = ctypes.c_int
 _lib.bload_plan.argtypes = [_vp, _i64, _i32, _u64, _vp, _vp, _vp, _vp,
                             ctypes.POINTER(_i64), ctypes.POINTER(_i64), _vp, _sz, _vp]
+_lib.bload_plan_shard.restype = ctypes.c_int
+_lib.bload_plan_shard.argtypes = [_vp, _vp, _vp, _i64, _i64, _i32, _i32, _vp, _vp, _vp,
+                                  ctypes.POINTER(_i64), ctypes.POINTER(_i64), _vp, _sz, _vp]
 _lib.bload_pack_workspace_bytes.restype = _sz
 _lib.bload_pack_workspace_bytes.argtypes = [_i64, _i32, _i64]
 _lib.bload_pack.restype = ctypes.c_int
@@ -135,6 +138,30 @@ def bload_plan(lengths: torch.Tensor, t_blk: int, seed: int, workspace: torch.Te
                          workspace.numel() * workspace.element_size(), _stream())
     _check(st)
     out.num_blocks, out.total_frames, out.t_blk = int(nb.value), int(tot.value), t_blk
+    return out
+
+
+def bload_plan_shard(plan: Plan, rank: int, world: int) -> Plan:
+    """Worker ``rank``'s share of ``plan`` (blocks rank mod world, plus a padding block for
+    the workers that would fall short) as a Plan in the worker's own block numbering.
+    Synchronises the current stream."""
+    n = plan.order.shape[0]
+    dev = plan.order.device
+    nb_local = -(-plan.num_blocks // world) if world > 0 else 0     # the library refuses world < 1
+    out = Plan(torch.empty(n, dtype=torch.int32, device=dev),
+               torch.empty(n, dtype=torch.int32, device=dev), plan.offset_of_seq,
+               torch.empty(nb_local + 1, dtype=torch.int32, device=dev), nb_local,
+               plan.total_frames, plan.t_blk)
+    ws = torch.empty(16, dtype=torch.uint8, device=dev)
+    nb, ns = _i64(0), _i64(0)
+    st = _lib.bload_plan_shard(_ptr(plan.order, torch.int32), _ptr(plan.block_of_seq, torch.int32),
+                               _ptr(plan.block_first, torch.int32), n, plan.num_blocks, rank, world,
+                               _ptr(out.order, torch.int32), _ptr(out.block_of_seq, torch.int32),
+                               _ptr(out.block_first, torch.int32), ctypes.byref(nb),
+                               ctypes.byref(ns), _ptr(ws), 16, _stream())
+    _check(st)
+    assert nb.value == nb_local
+    out.n_local = int(ns.value)
     return out
 
 

@@ -100,6 +100,14 @@ def test_argument_checks_need_no_gpu(lib):
     need = 4 * -(-180 * 600 * 37632 // 4096)         # one int32 per 4 KiB tile
     assert need <= f(180, 600, 37632) < need + 16 and f(180, 600, 37632) % 16 == 0
     assert f(180, 600, 4) == 4 * -(-180 * 600 // 1024) + 8 and f(0, 600, 4096) == 0
+    lib.bload_plan_shard.restype = ctypes.c_int
+    lib.bload_plan_shard.argtypes = [vp, vp, vp, i64, i64, i32, i32, vp, vp, vp,
+                                     ctypes.POINTER(i64), ctypes.POINTER(i64), vp, ctypes.c_size_t, vp]
+    assert lib.bload_plan_shard(p, p, p, 4, 2, 2, 2, p, p, p, nb, tot, p, 16, None) == 1     # rank >= world
+    assert lib.bload_plan_shard(p, p, p, 4, 2, 0, 0, p, p, p, nb, tot, p, 16, None) == 1     # world < 1
+    assert lib.bload_plan_shard(p, p, p, 4, 2, 0, 2, p, p, p, nb, tot, p, 8, None) == 3      # workspace
+    assert lib.bload_plan_shard(p, p, p, 0, 0, 0, 2, p, p, p, nb, tot, p, 16, None) == 0
+    assert (nb.value, tot.value) == (0, 0)
     lib.bload_segment_reduce.restype = ctypes.c_int
     lib.bload_segment_reduce.argtypes = [vp, vp, vp, vp, i64, i32, i64, ctypes.c_int, ctypes.c_int,
                                          i64, vp, vp, ctypes.c_size_t, vp]
