@@ -62,6 +62,10 @@ def _load():
         lib.bload_oracle_plan_shard.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_int64, ctypes.c_int64,
                                                                        ctypes.c_int32, ctypes.c_int32] + \
             [ctypes.c_void_p] * 3
+        lib.bload_oracle_segment_reduce_packed.restype = ctypes.c_int64
+        lib.bload_oracle_segment_reduce_packed.argtypes = [ctypes.c_void_p] * 4 + [
+            ctypes.c_int64, ctypes.c_int32, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int64,
+            ctypes.c_void_p]
         lib.bload_oracle_padding.restype = None
         lib.bload_oracle_padding.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
                                              ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
@@ -198,6 +202,21 @@ def segment_reduce(src, src_offsets, lengths, feat_dim: int, dtype: str, op: str
     if rc != 0:
         raise ValueError("unsupported dtype/op combination")
     return out
+
+
+def segment_reduce_packed(packed, seq_id, reset, valid, feat_dim: int, dtype: str, op: str,
+                          n_seq: int):
+    """Per-sequence sum / mean read from the packed blocks and their flags (any flags).
+    Returns (out[n_seq, feat_dim], number of segments); rows no segment names stay 0."""
+    B, T = seq_id.shape
+    pk = np.ascontiguousarray(packed).view(_NP_OF[dtype]).reshape(B, T, feat_dim)
+    sid, rs, vl = _c(seq_id, np.int32), _c(reset, np.uint8), _c(valid, np.uint8)
+    out = np.zeros((n_seq, feat_dim), dtype=np.int64 if dtype == "i32" else np.float32)
+    n = _load().bload_oracle_segment_reduce_packed(_p(pk), _p(sid), _p(rs), _p(vl), B, T, feat_dim,
+                                                   DTYPE_CODE[dtype], OP_CODE[op], n_seq, _p(out))
+    if n < 0:
+        raise ValueError("unsupported dtype/op combination")
+    return out, int(n)
 
 
 def padding(lengths, t_max: int, num_blocks: int, t_blk: int):

@@ -300,3 +300,69 @@ int64_t bload_oracle_plan_shard(const int32_t* order, const int32_t* block_of_se
     block_first_local[blocks_local] = (int32_t)n_local;
     return n_local;
 }
+
+/* ------------------------------------------------- reduce, from the blocks */
+
+/* The same per-sequence sum / mean, but read the way the consumer of the start
+ * table reads it (Methods section: reset the carried state where a new sequence
+ * starts): walk every block in time, carry a running sum, and restart it at a
+ * slot that is valid and (carries a start flag, or is the block's first slot, or
+ * follows a padding slot); a padding slot or the end of the block closes the
+ * running segment, whose result goes to row seq_id[first slot of the segment].
+ * Defined for any flags, not only those a correct pack writes.
+ * dtype / op / out as in bload_oracle_segment_reduce; rows that no segment names
+ * are left untouched.  Returns the number of segments, or -1 for i32 mean. */
+int64_t bload_oracle_segment_reduce_packed(const void* packed, const int32_t* seq_id,
+                                           const uint8_t* reset, const uint8_t* valid,
+                                           int64_t num_blocks, int32_t t_blk, int64_t feat_dim,
+                                           int dtype, int op, int64_t n_seq, void* out)
+{
+    if (dtype == 3 && op != 0) return -1;
+    int64_t segments = 0;
+    double* acc = (double*)malloc((size_t)(feat_dim > 0 ? feat_dim : 1) * sizeof(double));
+    int64_t* iacc = (int64_t*)malloc((size_t)(feat_dim > 0 ? feat_dim : 1) * sizeof(int64_t));
+    if (!acc || !iacc) { free(acc); free(iacc); return -2; }
+    for (int64_t b = 0; b < num_blocks; ++b) {
+        int open = 0;
+        int64_t count = 0;
+        int32_t row = -1;
+        for (int64_t t = 0; t <= t_blk; ++t) {
+            int64_t s = b * (int64_t)t_blk + t;
+            int is_valid = t < t_blk && valid[s] != 0;
+            int starts = is_valid && (reset[s] != 0 || t == 0 || valid[s - 1] == 0);
+            if (open && (!is_valid || starts)) {           /* the running segment ends before s */
+                if (row >= 0 && row < n_seq) {
+                    for (int64_t d = 0; d < feat_dim; ++d) {
+                        if (dtype == 3) {
+                            ((int64_t*)out)[row * feat_dim + d] = iacc[d];
+                        } else {
+                            double v = acc[d];
+                            if (op == 1) v /= (double)count;
+                            ((float*)out)[row * feat_dim + d] = (float)v;
+                        }
+                    }
+                }
+                segments += 1;
+                open = 0;
+            }
+            if (!is_valid) continue;
+            if (starts) {
+                open = 1;
+                count = 0;
+                row = seq_id[s];
+                for (int64_t d = 0; d < feat_dim; ++d) { acc[d] = 0.0; iacc[d] = 0; }
+            }
+            count += 1;
+            for (int64_t d = 0; d < feat_dim; ++d) {
+                int64_t e = s * feat_dim + d;
+                if (dtype == 0) acc[d] += (double)((const uint8_t*)packed)[e];
+                else if (dtype == 1) acc[d] += bload_oracle_half_to_double(((const uint16_t*)packed)[e]);
+                else if (dtype == 2) acc[d] += (double)((const float*)packed)[e];
+                else iacc[d] += (int64_t)((const int32_t*)packed)[e];
+            }
+        }
+    }
+    free(acc);
+    free(iacc);
+    return segments;
+}

@@ -104,3 +104,53 @@ def test_workload_reductions_have_the_expected_statistics():
     assert m.shape == (50, 80)
     assert abs(float(m.mean()) + 4.0) < 0.01
     assert float(np.abs(m + 4.0).max()) < 2.0 * 6 / np.sqrt(L.min())
+
+
+# ---- the reduction read from the packed blocks and their flags
+
+@pytest.mark.parametrize("dtype,np_dtype,op", [("u8", np.uint8, "mean"), ("f16", np.float16, "sum"),
+                                               ("f32", np.float32, "mean"), ("i32", np.int32, "sum")])
+def test_packed_reading_equals_the_ragged_definition(dtype, np_dtype, op):
+    # on what a correct pack writes, walking the blocks with resets at the start flags must
+    # give exactly the per-sequence reduction of the ragged source (both add in time order)
+    rng = np.random.default_rng(17)
+    n, T, D = 150, 40, 3
+    L = workloads.random_lengths(rng, n, T, "mixed")
+    so = workloads.src_offsets(L)
+    src = (rng.standard_normal((int(so[-1]), D)) * 50).astype(np_dtype)
+    pl = oracle.plan(L, T, oracle.order(n, 2))
+    packed, seq_id, frame_idx, reset, valid = oracle.pack(src, so, L, pl, D * src.dtype.itemsize)
+    want = oracle.segment_reduce(src, so, L, D, dtype, op)
+    got, nseg = oracle.segment_reduce_packed(packed, seq_id, reset, valid, D, dtype, op, n)
+    assert nseg == n
+    assert np.array_equal(got, want)
+    # garbage in the padding payload changes nothing
+    packed = packed.copy()
+    packed[valid == 0] = 0x5A
+    got2, _ = oracle.segment_reduce_packed(packed, seq_id, reset, valid, D, dtype, op, n)
+    assert np.array_equal(got2, want)
+
+
+def test_packed_reading_hand_worked_flags():
+    # one block of 10 slots, payload = slot number + 1, flags chosen by hand:
+    # slot     0  1  2  3  4  5  6  7  8  9
+    # valid    1  1  0  1  1  1  0  0  1  1
+    # reset    0  0  0  0  1  0  0  0  0  1
+    # segments [0,1] (block start)  [3] (after padding)  [4,5] (flag)  [8] (after padding)  [9] (flag)
+    valid = np.array([[1, 1, 0, 1, 1, 1, 0, 0, 1, 1]], dtype=np.uint8)
+    reset = np.array([[0, 0, 0, 0, 1, 0, 0, 0, 0, 1]], dtype=np.uint8)
+    seq_id = np.array([[0, 0, -1, 1, 2, 2, -1, -1, 3, 4]], dtype=np.int32)
+    packed = (np.arange(10, dtype=np.int32) + 1).reshape(1, 10, 1)
+    got, nseg = oracle.segment_reduce_packed(packed, seq_id, reset, valid, 1, "i32", "sum", 6)
+    assert nseg == 5
+    assert got[:, 0].tolist() == [1 + 2, 4, 5 + 6, 9, 10, 0]
+    gotf, _ = oracle.segment_reduce_packed(packed.astype(np.float32), seq_id, reset, valid, 1, "f32",
+                                           "mean", 6)
+    assert gotf[:, 0].tolist() == [1.5, 4.0, 5.5, 9.0, 10.0, 0.0]
+    # two blocks never share a segment: the same flags twice, second block without any start flag
+    valid2 = np.ones((2, 4), dtype=np.uint8)
+    reset2 = np.zeros((2, 4), dtype=np.uint8)
+    seq2 = np.array([[0, 0, 0, 0], [1, 1, 1, 1]], dtype=np.int32)
+    pk2 = np.arange(8, dtype=np.int32).reshape(2, 4, 1)
+    got2, nseg2 = oracle.segment_reduce_packed(pk2, seq2, reset2, valid2, 1, "i32", "sum", 2)
+    assert nseg2 == 2 and got2[:, 0].tolist() == [0 + 1 + 2 + 3, 4 + 5 + 6 + 7]
