@@ -175,9 +175,9 @@ template <typename ElemT, int VEC>
 __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
 {
     typedef typename Elem<ElemT>::Acc Acc;
-    extern __shared__ uint8_t s_flags[];   // rows x (chunk + 1): bit0 valid, bit1 reset
+    extern __shared__ uint8_t s_flags[];   // rows x (chunk + 2): bit0 valid, bit1 reset
     const int tid = (int)threadIdx.x;
-    const int C = a.chunk, stride = C + 1;
+    const int C = a.chunk, stride = C + 2;
     const int rows = kThreads >> a.row_lanes_log2;
     // consecutive workgroups take the lane-slices of one frame range, so that
     // workgroups running side by side read neighbouring memory
@@ -185,7 +185,8 @@ __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
     const int64_t q_base = (int64_t)(blockIdx.x / (uint32_t)a.feat_tiles) * rows;
     const int64_t T = a.t_blk;
 
-    // stage the flags of this workgroup's chunks, plus the slot after each chunk
+    // stage the flags of this workgroup's chunks, plus the slot before and the slot
+    // after each chunk (0 outside the block): row r holds slots t0-1 .. t0+len
     for (int r = 0; r < rows; ++r) {
         const int64_t q = q_base + r;
         if (q >= a.total_chunks) break;
@@ -193,10 +194,11 @@ __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
         const int32_t t0 = (int32_t)(q - b * a.n_chunks) * C;
         const int32_t len = min(C, a.t_blk - t0);
         const int64_t g = b * T + t0;
-        for (int t = tid; t <= len; t += kThreads) {
+        for (int t = tid - 1; t <= len; t += kThreads) {
             uint8_t f = 0;
-            if (t0 + t < a.t_blk) f = (uint8_t)((a.valid[g + t] ? 1 : 0) | (a.reset[g + t] ? 2 : 0));
-            s_flags[r * stride + t] = f;
+            if (t0 + t >= 0 && t0 + t < a.t_blk)
+                f = (uint8_t)((a.valid[g + t] ? 1 : 0) | (a.reset[g + t] ? 2 : 0));
+            s_flags[r * stride + 1 + t] = f;
         }
     }
     __syncthreads();
@@ -215,7 +217,7 @@ __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
     const int32_t t0 = (int32_t)(q - b * a.n_chunks) * C;
     const int32_t len = min(C, a.t_blk - t0);
     const int64_t g = b * T + t0;
-    const uint8_t* flags = s_flags + row * stride;
+    const uint8_t* flags = s_flags + row * stride + 1;      // flags[-1] = the slot before the chunk
     const int64_t frame_bytes = (int64_t)a.feat_dim * (int64_t)sizeof(ElemT);
     const uint8_t* lane_src = a.packed + g * frame_bytes + (int64_t)fv * VEC * (int64_t)sizeof(ElemT);
     const int64_t feat0 = (int64_t)fv * VEC;
@@ -244,9 +246,10 @@ __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
     for (;;) {
         t = next_slot<true>(flags, t, len, a.row_lanes_log2);           // next valid slot
         if (t >= len) break;
-        const bool starts = (flags[t] & 2) || (t0 + t == 0);
-        // a valid first slot without a start flag continues the previous chunk's segment
-        const bool head_open = !starts && t == 0;
+        // a segment starts at a start flag, at the block's first slot, or behind padding;
+        // a valid first slot of the chunk that does none of these continues the segment
+        // of the chunk before
+        const bool head_open = t == 0 && !(flags[0] & 2) && (flags[-1] & 1);
         const int32_t e = next_slot<false>(flags, t + 1, len, a.row_lanes_log2);  // padding or a start
 #pragma unroll
         for (int k = 0; k < VEC; ++k) acc[k] = 0;
@@ -744,7 +747,7 @@ static ReducePlan reduce_plan(int64_t num_blocks, int32_t t_blk, int64_t feat_di
         if (want > most) want = most;
         if (want < 1) want = 1;
         int64_t chunk = ceil_div(t_blk, want);
-        const int64_t lds_cap = kWideFlagBytes / rows - 1;
+        const int64_t lds_cap = kWideFlagBytes / rows - 2;
         if (chunk > lds_cap) chunk = lds_cap;
         p.chunk = (int32_t)chunk;
         p.n_chunks = (int32_t)ceil_div(t_blk, chunk);
@@ -772,7 +775,7 @@ static void launch_wide(const ReducePlan& p, const ReduceArgs& a, hipStream_t st
 {
     const int rows = kThreads >> p.row_lanes_log2;
     const dim3 grid((uint32_t)(ceil_div(p.total_chunks, rows) * a.feat_tiles));
-    size_t lds = (size_t)rows * (size_t)(p.chunk + 1);
+    size_t lds = (size_t)rows * (size_t)(p.chunk + 2);
     if (p.vec > 1 && p.row_lanes_log2 >= 6)     // + the per-wave scratch of the transposed stores
         lds = round_up(lds, 16) + (size_t)(kThreads / kWave) * kWave * (p.vec + 1) *
                                       sizeof(typename Elem<ElemT>::Acc);

@@ -147,3 +147,50 @@ def test_reduce_workloads_full_size(wid):
                                   w.n_seq)
     torch.cuda.synchronize()
     check_reduction(red.cpu().numpy(), src, so, L, w.frame_elems, w.dtype, w.op)
+
+
+# ---- arbitrary flags: the consumer's rule, not only what a correct pack writes
+
+def random_flags(rng, B, T, p_valid, p_reset):
+    """valid / reset planes with runs of padding anywhere, start flags anywhere, and a seq_id
+    plane that gives every segment of the consumer's rule its own row."""
+    valid = (rng.random((B, T)) < p_valid).astype(np.uint8)
+    # make padding come in runs so that long segments exist too
+    keep = rng.random((B, T)) < 0.9
+    for t in range(1, T):
+        valid[:, t] = np.where(keep[:, t], valid[:, t - 1], valid[:, t])
+    reset = ((rng.random((B, T)) < p_reset) & (valid == 1)).astype(np.uint8)
+    prev_valid = np.concatenate([np.zeros((B, 1), np.uint8), valid[:, :-1]], axis=1)
+    starts = (valid == 1) & ((reset == 1) | (prev_valid == 0))
+    starts[:, 0] = valid[:, 0] == 1
+    ids = np.cumsum(starts.reshape(-1)).reshape(B, T) - 1
+    seq_id = np.where(valid == 1, ids, -1).astype(np.int32)
+    return valid, reset, seq_id, int(starts.sum())
+
+
+@pytest.mark.parametrize("dtype,op", [("f32", "mean"), ("i32", "sum"), ("u8", "sum"), ("f16", "mean")])
+@pytest.mark.parametrize("B,T,D", [(3, 10, 1), (700, 33, 1), (40, 5000, 1), (9, 4096, 2),
+                                   (300, 130, 16), (50, 700, 80), (20, 3000, 256), (64, 32, 3072)])
+def test_reduce_follows_the_flags(B, T, D, dtype, op):
+    bl = binding()
+    rng = np.random.default_rng(B + T + D)
+    for p_valid, p_reset in [(0.85, 0.02), (0.5, 0.3), (1.0, 0.0)]:
+        valid, reset, seq_id, n_seg = random_flags(rng, B, T, p_valid, p_reset)
+        src = draw_source(rng, B * T, D, dtype)          # payload in every slot, padding included
+        packed = src.reshape(B, T, D)
+        want, counted = oracle.segment_reduce_packed(packed, seq_id, reset, valid, D, dtype, op, n_seg)
+        assert counted == n_seg
+        print(f"flags B={B} T={T} D={D} {dtype} {op} valid~{p_valid} reset~{p_reset} segments={n_seg}",
+              flush=True)
+        if n_seg == 0:
+            continue
+        got = bl.bload_segment_reduce(to_dev(packed), to_dev(seq_id), to_dev(reset), to_dev(valid),
+                                      B, T, D, dtype, op, n_seg).cpu().numpy()
+        if dtype == "i32":
+            assert np.array_equal(got, want)
+            continue
+        absval = np.abs(packed.astype(np.float64)).astype(np.float32)
+        scale, _ = oracle.segment_reduce_packed(absval, seq_id, reset, valid, D, "f32", op, n_seg)
+        bound = REL_TOL * np.maximum(np.abs(want.astype(np.float64)), scale.astype(np.float64)) + 1e-30
+        err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+        assert np.all(err <= bound), f"max err {err.max()} at {np.unravel_index(np.argmax(err - bound), err.shape)}"
