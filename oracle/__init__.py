@@ -66,6 +66,9 @@ def _load():
         lib.bload_oracle_segment_reduce_packed.argtypes = [ctypes.c_void_p] * 4 + [
             ctypes.c_int64, ctypes.c_int32, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int64,
             ctypes.c_void_p]
+        lib.bload_oracle_plan_random_fit.restype = ctypes.c_int
+        lib.bload_oracle_plan_random_fit.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
+                                                     ctypes.c_uint64] + [ctypes.c_void_p] * 7
         lib.bload_oracle_padding.restype = None
         lib.bload_oracle_padding.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
                                              ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
@@ -128,6 +131,28 @@ def plan(lengths, t_blk: int, order_) -> Plan:
     tot = np.zeros(1, dtype=np.int64)
     rc = _load().bload_oracle_plan(_p(L), n, t_blk, _p(o), _p(block_of), _p(offset_of),
                                    _p(block_first), _p(nb), _p(tot))
+    if rc != 0:
+        raise ValueError("length outside [1, t_blk]")
+    b = int(nb[0])
+    return Plan(o, block_of, offset_of, block_first[:b + 1].copy() if n else block_first[:0],
+                b, int(tot[0]), t_blk)
+
+
+def plan_random_fit(lengths, t_blk: int, seed: int) -> Plan:
+    """The paper's sampler: each block draws uniformly among the remaining sequences that
+    still fit until none does.  Raises ValueError on a length outside [1, t_blk]."""
+    L = _c(lengths, np.int32)
+    n = L.shape[0]
+    seeded = order(n, seed)
+    o = np.full(n, -7, dtype=np.int32)
+    block_of = np.full(n, -7, dtype=np.int32)
+    offset_of = np.full(n, -7, dtype=np.int32)
+    block_first = np.full(n + 1, -7, dtype=np.int32)
+    nb = np.zeros(1, dtype=np.int64)
+    tot = np.zeros(1, dtype=np.int64)
+    rc = _load().bload_oracle_plan_random_fit(_p(L), n, t_blk, seed & (2**64 - 1), _p(seeded), _p(o),
+                                              _p(block_of), _p(offset_of), _p(block_first), _p(nb),
+                                              _p(tot))
     if rc != 0:
         raise ValueError("length outside [1, t_blk]")
     b = int(nb[0])

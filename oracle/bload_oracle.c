@@ -27,6 +27,8 @@
  *              ragged source, so it does not depend on plan or pack.
  *   - padding: Problem Statement (padding every sample to the longest one)
  *              and Table 1 ("padding amount").
+ *   - shard:   Problem Statement: equal sample counts for all data-parallel workers.
+ *   - random fit: the sampler named in the caption of the pseudocode figure.
  *
  * Parity pins (tests/test_oracle_*.py): SplitMix64 known answers, invertible
  * finaliser, bijectivity and spread of the order; next-fit invariants, closed
@@ -365,4 +367,81 @@ int64_t bload_oracle_segment_reduce_packed(const void* packed, const int32_t* se
     free(acc);
     free(iacc);
     return segments;
+}
+
+/* ------------------------------------------------------------- random fit */
+
+/* The block builder of the paper's pseudocode figure, whose caption fixes the
+ * sampler: it returns a random entry of the length dictionary L_dict among those
+ * whose sequence is no longer than the frames remaining in the open block.  A block
+ * is closed when no remaining sequence fits (or none remains).
+ *
+ * What the caption leaves open, as read here:
+ *   - "random entry": every remaining sequence that fits is equally likely.  With m
+ *     such sequences the draw is k = floor(u * m / 2^64) for a 64-bit uniform u, and
+ *     the k-th of them counted through L_dict by ascending length is taken.
+ *   - u for the p-th placement (p = 0, 1, ...) is output number 6 + p of the SplitMix64
+ *     stream started at the seed (outputs 0..5 key the seeded order).
+ *   - L_dict[l] lists the sequences of length l in the seeded order; a draw that lands
+ *     in L_dict[l] removes the last remaining entry of that list.  Since the seeded
+ *     order is itself a random permutation this picks uniformly inside the class.
+ *
+ * `seeded` is the seeded order (bload_oracle_order).  Outputs as in bload_oracle_plan:
+ * order[p] is the p-th sequence placed.  Returns 0, or 2 on a length outside [1, t_blk]. */
+int bload_oracle_plan_random_fit(const int32_t* lengths, int64_t n, int32_t t_blk, uint64_t seed,
+                                 const int32_t* seeded, int32_t* order, int32_t* block_of_seq,
+                                 int32_t* offset_of_seq, int32_t* block_first,
+                                 int64_t* num_blocks, int64_t* total_frames)
+{
+    *num_blocks = 0;
+    *total_frames = 0;
+    for (int64_t i = 0; i < n; ++i)
+        if (lengths[i] < 1 || lengths[i] > t_blk) return 2;
+    if (n <= 0) return 0;
+
+    /* L_dict: entry[first[l] .. first[l] + left[l]) are the remaining sequences of length l */
+    int64_t* left = calloc((size_t)t_blk + 2, sizeof(int64_t));
+    int64_t* first = calloc((size_t)t_blk + 2, sizeof(int64_t));
+    int32_t* entry = malloc((size_t)n * sizeof(int32_t));
+    int64_t total = 0;
+    for (int64_t i = 0; i < n; ++i) { left[lengths[i]] += 1; total += lengths[i]; }
+    for (int64_t l = 1; l <= t_blk; ++l) first[l + 1] = first[l] + left[l];
+    for (int64_t l = 0; l <= t_blk; ++l) left[l] = 0;
+    for (int64_t p = 0; p < n; ++p) {
+        int32_t i = seeded[p];
+        int64_t l = lengths[i];
+        entry[first[l] + left[l]] = i;
+        left[l] += 1;
+    }
+
+    int64_t placed = 0;
+    int64_t b = 0;
+    while (placed < n) {
+        int64_t remaining_frames = t_blk;
+        block_first[b] = (int32_t)placed;
+        for (;;) {
+            uint64_t m = 0;                               /* sequences that still fit */
+            for (int64_t l = 1; l <= remaining_frames; ++l) m += (uint64_t)left[l];
+            if (m == 0) break;
+            uint64_t u = bload_oracle_splitmix64(seed, (uint64_t)(6 + placed));
+            uint64_t k = (uint64_t)(((unsigned __int128)u * m) >> 64);
+            int64_t l = 1;
+            while (k >= (uint64_t)left[l]) { k -= (uint64_t)left[l]; ++l; }
+            left[l] -= 1;
+            int32_t i = entry[first[l] + left[l]];
+            order[placed] = i;
+            block_of_seq[i] = (int32_t)b;
+            offset_of_seq[i] = (int32_t)(t_blk - remaining_frames);
+            remaining_frames -= l;
+            placed += 1;
+        }
+        b += 1;
+    }
+    block_first[b] = (int32_t)n;
+    *num_blocks = b;
+    *total_frames = total;
+    free(left);
+    free(first);
+    free(entry);
+    return 0;
 }
