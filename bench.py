@@ -2,11 +2,13 @@
 """Benchmark of the BLoad block packer on one MI355X.
 
 A step is one pass of the whole path over one synthetic workload that is
-already resident in HBM: bload_plan (order + next-fit), bload_pack (gather,
+already resident in HBM: bload_plan (order + next-fit; --plan random-fit takes
+the paper's sampler instead), bload_pack (gather,
 zero padding, start table) and bload_segment_reduce (per-sequence reduction
 over the packed blocks).  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2] [--plan next-fit]
+                    [--no-cpu-baseline]
 
 value      valid frames packed per second over the whole path (all K steps)
 roofline   the gather/pad kernel against the HBM roofline: algorithmic bytes
@@ -52,6 +54,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--plan", choices=["next-fit", "random-fit"], default="next-fit",
+                    help="block builder: next-fit over the seeded order (default, parallel) or the "
+                         "paper's sampler, uniform among the remaining sequences that fit "
+                         "(bload_plan_random_fit, a sequential chain of draws)")
     ap.add_argument("--world", type=int, default=1,
                     help="time the share of one data-parallel worker (blocks rank mod world, "
                          "bload_plan_shard) instead of the whole workload; still one GPU")
@@ -84,8 +90,12 @@ def main() -> int:
     seed = 0
 
     # everything the steps write is allocated once, outside the timed region
-    plan_ws = torch.empty(max(16, bload.bload_plan_workspace_bytes(N)), dtype=torch.uint8, device=dev)
-    plan = bload.bload_plan(d_L, T, seed, workspace=plan_ws)
+    if args.plan == "random-fit":
+        make_plan, plan_ws_bytes = bload.bload_plan_random_fit, bload.bload_plan_random_fit_workspace_bytes(N)
+    else:
+        make_plan, plan_ws_bytes = bload.bload_plan, bload.bload_plan_workspace_bytes(N)
+    plan_ws = torch.empty(max(16, plan_ws_bytes), dtype=torch.uint8, device=dev)
+    plan = make_plan(d_L, T, seed, workspace=plan_ws)
     sharded = args.world > 1
     if sharded:
         share = bload.bload_plan_shard(plan, args.rank, args.world)
@@ -107,7 +117,7 @@ def main() -> int:
     def step(events=None):
         if events:
             events[0].record()
-        bload.bload_plan(d_L, T, seed, workspace=plan_ws, out=plan)
+        make_plan(d_L, T, seed, workspace=plan_ws, out=plan)
         todo = bload.bload_plan_shard(plan, args.rank, args.world) if sharded else plan
         if events:
             events[1].record()
@@ -151,7 +161,9 @@ def main() -> int:
     pad_blocks = slots - work_frames
     pad_longest = local_seqs * T - work_frames
     kernel_src = os.path.join(ROOT, "paper_2310_10879_amd", "csrc", "bload_pack.hip")
-    traffic = measured_traffic(kernel_src, w.wid)
+    # the committed counters were taken on the whole workload under the next-fit plan
+    traffic = (measured_traffic(kernel_src, w.wid)
+               if args.plan == "next-fit" and not sharded else None)
 
     result = {
         "metric": "packed_frames_per_s",
@@ -167,7 +179,8 @@ def main() -> int:
         "dtype": w.dtype,
         "data": "synthetic",
         "config": {
-            "workload": f"{w.wid}: N={N} {w.name}, T_blk={T}, frame_bytes={F}, seed={seed}"
+            "workload": f"{w.wid}: N={N} {w.name}, T_blk={T}, frame_bytes={F}, seed={seed}, "
+                        f"{args.plan} plan"
                         + (f", share of worker {args.rank} of {args.world}" if sharded else ""),
             "n_seq": N, "t_blk": T, "frame_bytes": F, "total_frames": total_frames,
             "num_blocks": B, "lengths": "lognormal(mu=ln 60, sigma=1) clipped to [1,600]"
@@ -209,7 +222,8 @@ def main() -> int:
         # the oracle as it stands, one thread: order + plan + pack + reduce of the same workload
         out = oracle.alloc_pack_outputs(B, T, F)
         c0 = time.perf_counter()
-        ref_plan = oracle.plan(L, T, oracle.order(N, seed))
+        ref_plan = (oracle.plan_random_fit(L, T, seed) if args.plan == "random-fit"
+                    else oracle.plan(L, T, oracle.order(N, seed)))
         c1 = time.perf_counter()
         oracle.pack(src, so, L, ref_plan, F, out=out)
         c2 = time.perf_counter()

@@ -104,6 +104,36 @@ bload_status bload_plan(const int32_t* d_lengths, int64_t n_seq, int32_t t_blk, 
                         int64_t* h_num_blocks, int64_t* h_total_frames,
                         void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ------------------------------------------------------- plan, random fit --
+ * Caption of the pseudocode figure: the block builder asks a sampler for a random
+ * entry of the length dictionary L_dict among the sequences no longer than the
+ * frames remaining in the open block; a block is closed when none fits.  The
+ * reading implemented here:
+ *   - every remaining sequence that fits is equally likely: with m of them the
+ *     draw is k = floor(u * m / 2^64), u the output number 6 + p of the seed's
+ *     SplitMix64 stream for the p-th placement, and the k-th is counted through
+ *     L_dict by ascending length;
+ *   - L_dict[l] lists the sequences of length l in the seeded order (the order
+ *     bload_plan visits them in); a draw landing in L_dict[l] takes its last
+ *     remaining entry.
+ * Arguments, outputs, workspace rules and error codes are those of bload_plan
+ * (d_order[p] is the p-th sequence placed); bload_pack, bload_plan_shard and
+ * bload_segment_reduce take the result like a next-fit plan.  Additionally
+ * BLOAD_EOVERFLOW when t_blk > BLOAD_RANDOM_FIT_MAX_T_BLK (the per-length counts
+ * are kept in on-chip memory).  The draws form a dependent chain that one
+ * wavefront walks: the cost grows linearly with n_seq.
+ * Synchronises the stream before returning.
+ */
+#define BLOAD_RANDOM_FIT_MAX_T_BLK 8192
+
+size_t bload_plan_random_fit_workspace_bytes(int64_t n_seq);
+
+bload_status bload_plan_random_fit(const int32_t* d_lengths, int64_t n_seq, int32_t t_blk,
+                                   uint64_t seed, int32_t* d_order, int32_t* d_block_of_seq,
+                                   int32_t* d_offset_of_seq, int32_t* d_block_first,
+                                   int64_t* h_num_blocks, int64_t* h_total_frames,
+                                   void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
 /* ------------------------------------------------------------ plan shard --
  * Problem Statement: under data-parallel training every worker must receive the
  * same number of samples per epoch, otherwise the gradient exchange stalls; the

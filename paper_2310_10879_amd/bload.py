@@ -42,6 +42,10 @@ _lib.bload_plan_workspace_bytes.argtypes = [_i64]
 _lib.bload_plan.restype = ctypes.c_int
 _lib.bload_plan.argtypes = [_vp, _i64, _i32, _u64, _vp, _vp, _vp, _vp,
                             ctypes.POINTER(_i64), ctypes.POINTER(_i64), _vp, _sz, _vp]
+_lib.bload_plan_random_fit_workspace_bytes.restype = _sz
+_lib.bload_plan_random_fit_workspace_bytes.argtypes = [_i64]
+_lib.bload_plan_random_fit.restype = ctypes.c_int
+_lib.bload_plan_random_fit.argtypes = list(_lib.bload_plan.argtypes)
 _lib.bload_plan_shard.restype = ctypes.c_int
 _lib.bload_plan_shard.argtypes = [_vp, _vp, _vp, _i64, _i64, _i32, _i32, _vp, _vp, _vp,
                                   ctypes.POINTER(_i64), ctypes.POINTER(_i64), _vp, _sz, _vp]
@@ -136,6 +140,37 @@ def bload_plan(lengths: torch.Tensor, t_blk: int, seed: int, workspace: torch.Te
                          _ptr(out.offset_of_seq, torch.int32), _ptr(out.block_first, torch.int32),
                          ctypes.byref(nb), ctypes.byref(tot), _ptr(workspace),
                          workspace.numel() * workspace.element_size(), _stream())
+    _check(st)
+    out.num_blocks, out.total_frames, out.t_blk = int(nb.value), int(tot.value), t_blk
+    return out
+
+
+def bload_plan_random_fit_workspace_bytes(n_seq: int) -> int:
+    return int(_lib.bload_plan_random_fit_workspace_bytes(n_seq))
+
+
+def bload_plan_random_fit(lengths: torch.Tensor, t_blk: int, seed: int,
+                          workspace: torch.Tensor | None = None, out: Plan | None = None) -> Plan:
+    """The plan built with the paper's sampler (uniform among the remaining sequences that
+    still fit the open block).  lengths: int32[N] on the device.  Synchronises the current
+    stream."""
+    n = lengths.shape[0]
+    dev = lengths.device
+    if out is None:
+        out = Plan(torch.empty(n, dtype=torch.int32, device=dev),
+                   torch.empty(n, dtype=torch.int32, device=dev),
+                   torch.empty(n, dtype=torch.int32, device=dev),
+                   torch.empty(n + 1, dtype=torch.int32, device=dev), 0, 0, t_blk)
+    if workspace is None:
+        workspace = torch.empty(max(bload_plan_random_fit_workspace_bytes(n), 16), dtype=torch.uint8,
+                                device=dev)
+    nb, tot = _i64(0), _i64(0)
+    st = _lib.bload_plan_random_fit(_ptr(lengths, torch.int32), n, t_blk, seed & (2**64 - 1),
+                                    _ptr(out.order, torch.int32), _ptr(out.block_of_seq, torch.int32),
+                                    _ptr(out.offset_of_seq, torch.int32),
+                                    _ptr(out.block_first, torch.int32), ctypes.byref(nb),
+                                    ctypes.byref(tot), _ptr(workspace),
+                                    workspace.numel() * workspace.element_size(), _stream())
     _check(st)
     out.num_blocks, out.total_frames, out.t_blk = int(nb.value), int(tot.value), t_blk
     return out

@@ -85,6 +85,24 @@ def test_argument_checks_need_no_gpu(lib):
     assert lib.bload_plan(p, (1 << 27) + 1, 8, 0, p, p, p, p, nb, tot, p, 1 << 20, None) == 5
     assert lib.bload_plan(p, 0, 8, 0, p, p, p, p, nb, tot, p, 0, None) == 0
     assert (nb.value, tot.value) == (0, 0)
+    rf = lib.bload_plan_random_fit
+    rf.restype = ctypes.c_int
+    rf.argtypes = lib.bload_plan.argtypes
+    nb.value = tot.value = 7
+    assert rf(p, -1, 8, 0, p, p, p, p, nb, tot, p, 1 << 20, None) == 1
+    assert rf(p, 4, 0, 0, p, p, p, p, nb, tot, p, 1 << 20, None) == 1
+    assert rf(None, 4, 8, 0, p, p, p, p, nb, tot, p, 1 << 20, None) == 1
+    assert rf(p, 4, 8, 0, p, p, p, p, nb, tot, p, 8, None) == 3
+    assert rf(p, 4, 8, 0, p, p + 2, p, p, nb, tot, p, 1 << 20, None) == 4
+    assert rf(p, 4, 8193, 0, p, p, p, p, nb, tot, p, 1 << 20, None) == 5       # t_blk beyond the on-chip counts
+    assert rf(p, (1 << 27) + 1, 8, 0, p, p, p, p, nb, tot, p, 1 << 20, None) == 5
+    assert rf(p, 0, 8, 0, p, p, p, p, nb, tot, p, 0, None) == 0
+    assert (nb.value, tot.value) == (0, 0)
+    w = lib.bload_plan_random_fit_workspace_bytes
+    w.restype = ctypes.c_size_t
+    w.argtypes = [i64]
+    assert w(-1) == 0 and w((1 << 27) + 1) == 0 and w(1000) % 16 == 0
+    assert 28 * 10**6 <= w(10**6) <= 28 * 10**6 + 70000
     lib.bload_pack.restype = ctypes.c_int
     lib.bload_pack.argtypes = [vp] * 7 + [i64, i64, i32, i64] + [vp] * 6 + [ctypes.c_size_t, vp]
     ok = [p] * 7 + [4, 2, 8, 16] + [p] * 5 + [p, 1 << 20, None]
