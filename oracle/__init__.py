@@ -73,6 +73,9 @@ def _load():
         lib.bload_oracle_padding.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
                                              ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
                                              ctypes.c_void_p]
+        lib.bload_oracle_chunk_sampling.restype = None
+        lib.bload_oracle_chunk_sampling.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                                                    ctypes.c_void_p, ctypes.c_void_p]
         _lib = lib
     return _lib
 
@@ -250,4 +253,13 @@ def padding(lengths, t_max: int, num_blocks: int, t_blk: int):
     a = np.zeros(1, dtype=np.int64)
     b = np.zeros(1, dtype=np.int64)
     _load().bload_oracle_padding(_p(L), L.shape[0], t_max, num_blocks, t_blk, _p(a), _p(b))
+    return int(a[0]), int(b[0])
+
+
+def chunk_sampling(lengths, t_chunk: int):
+    """(samples, frames deleted) when every sequence is cut into pieces of t_chunk frames."""
+    L = _c(lengths, np.int32)
+    a = np.zeros(1, dtype=np.int64)
+    b = np.zeros(1, dtype=np.int64)
+    _load().bload_oracle_chunk_sampling(_p(L), L.shape[0], t_chunk, _p(a), _p(b))
     return int(a[0]), int(b[0])

@@ -445,3 +445,26 @@ int bload_oracle_plan_random_fit(const int32_t* lengths, int64_t n, int32_t t_bl
     free(entry);
     return 0;
 }
+
+/* -------------------------------------------------------- chunk sampling */
+
+/* The second baseline of the Problem Statement (and Table 1's "sampling" column,
+ * rows "padding amount" = 0 and "# frames deleted"): every sequence is cut into
+ * pieces of t_chunk frames and each piece is a sample of its own; nothing is padded,
+ * so whatever does not fill a piece is deleted.
+ *   samples = sum over sequences of floor(L / t_chunk)
+ *   deleted = sum over sequences of L mod t_chunk */
+void bload_oracle_chunk_sampling(const int32_t* lengths, int64_t n, int64_t t_chunk,
+                                 int64_t* samples, int64_t* deleted)
+{
+    int64_t s = 0, d = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t whole = 0;
+        int64_t left = lengths[i];
+        while (left >= t_chunk) { left -= t_chunk; whole += 1; }
+        s += whole;
+        d += left;
+    }
+    *samples = s;
+    *deleted = d;
+}
