@@ -165,6 +165,11 @@ def main() -> int:
     traffic = (measured_traffic(kernel_src, w.wid)
                if args.plan == "next-fit" and not sharded else None)
 
+    # the strategies of the paper's Table 1 on the same lengths (outside the timed region)
+    t_chunk = max(1, total_frames // N)               # pieces of the average length
+    strategies = bload.bload_strategy_counts(d_L, t_chunk, T, plan.num_blocks, T)
+    strategies["t_chunk"] = t_chunk
+
     result = {
         "metric": "packed_frames_per_s",
         "value": work_frames * args.steps / elapsed,
@@ -204,6 +209,7 @@ def main() -> int:
             "pad_ratio_to_longest": pad_longest / (local_seqs * T),
             "reduction_vs_pad_to_longest": pad_longest / max(1, pad_blocks),
         },
+        "strategy_counts": strategies,
         "roofline": {
             "kernel": "pack_wide_kernel" if F >= 512 else "pack_narrow_kernel",
             "bound": "hbm",

@@ -238,6 +238,40 @@ bload_status bload_segment_reduce(const void* d_packed, const int32_t* d_seq_id,
                                   bload_dtype dtype, bload_op op, int64_t n_seq, void* d_out,
                                   void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ------------------------------------------------------- strategy counts --
+ * Problem Statement and Table 1 (rows "padding amount" and "# frames deleted"):
+ * what the strategies compared there cost on a given set of lengths, counted in
+ * frames, without materialising anything.
+ *   pad to the longest  every sequence padded to t_max:  n_seq * t_max - sum(L)
+ *   chunk sampling      every sequence cut into pieces of t_chunk frames, each a
+ *                       sample of its own, nothing padded: sum(floor(L / t_chunk))
+ *                       samples, sum(L mod t_chunk) frames deleted
+ *   block packing       num_blocks * t_blk - sum(L), for the plan's num_blocks
+ * ("mix pad" of Table 1 is not defined in the paper and is not counted.)
+ *
+ * d_lengths   in   int32[n_seq], every L >= 0
+ * t_max       in   pad-to-longest target; <= 0 means "the longest sequence found"
+ * t_chunk     in   >= 1
+ * num_blocks, t_blk   in   as returned by / given to a planner (0, 0 to skip)
+ * h_counts    out  host struct, see below
+ * d_workspace      >= 64 bytes, 16-byte aligned
+ *
+ * Synchronises the stream before returning.
+ */
+typedef struct bload_strategy_counts_t {
+    int64_t total_frames;       /* sum(L) */
+    int64_t longest;            /* max(L), 0 when n_seq == 0 */
+    int64_t pad_to_longest;     /* frames of padding when every sequence is padded */
+    int64_t pad_blocks;         /* frames of padding in the packed blocks */
+    int64_t chunk_samples;      /* pieces of t_chunk frames */
+    int64_t chunk_deleted;      /* frames that fill no piece */
+} bload_strategy_counts_t;
+
+bload_status bload_strategy_counts(const int32_t* d_lengths, int64_t n_seq, int32_t t_max,
+                                   int32_t t_chunk, int64_t num_blocks, int32_t t_blk,
+                                   bload_strategy_counts_t* h_counts, void* d_workspace,
+                                   size_t workspace_bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -54,6 +54,21 @@ _lib.bload_pack_workspace_bytes.argtypes = [_i64, _i32, _i64]
 _lib.bload_pack.restype = ctypes.c_int
 _lib.bload_pack.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i32, _i64,
                             _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+
+
+class StrategyCounts(ctypes.Structure):
+    """bload_strategy_counts_t"""
+    _fields_ = [(name, ctypes.c_int64) for name in
+                ("total_frames", "longest", "pad_to_longest", "pad_blocks", "chunk_samples",
+                 "chunk_deleted")]
+
+    def as_dict(self) -> dict:
+        return {name: int(getattr(self, name)) for name, _ in self._fields_}
+
+
+_lib.bload_strategy_counts.restype = ctypes.c_int
+_lib.bload_strategy_counts.argtypes = [_vp, _i64, _i32, _i32, _i64, _i32,
+                                       ctypes.POINTER(StrategyCounts), _vp, _sz, _vp]
 _lib.bload_segment_reduce_workspace_bytes.restype = _sz
 _lib.bload_segment_reduce_workspace_bytes.argtypes = [_i64, _i32, _i64, ctypes.c_int]
 _lib.bload_segment_reduce.restype = ctypes.c_int
@@ -270,3 +285,18 @@ def bload_segment_reduce(packed: torch.Tensor, seq_id: torch.Tensor, reset: torc
                                    workspace.numel() * workspace.element_size(), _stream())
     _check(st)
     return out
+
+
+def bload_strategy_counts(lengths: torch.Tensor, t_chunk: int, t_max: int = 0, num_blocks: int = 0,
+                          t_blk: int = 0, workspace: torch.Tensor | None = None) -> dict:
+    """Frames of padding / frames deleted under padding to the longest sequence, chunk sampling
+    with pieces of ``t_chunk`` frames, and block packing (``num_blocks`` x ``t_blk``).
+    ``t_max`` <= 0 pads to the longest sequence found.  Synchronises the current stream."""
+    if workspace is None:
+        workspace = torch.empty(64, dtype=torch.uint8, device=lengths.device)
+    out = StrategyCounts()
+    st = _lib.bload_strategy_counts(_ptr(lengths, torch.int32), lengths.shape[0], t_max, t_chunk,
+                                    num_blocks, t_blk, ctypes.byref(out), _ptr(workspace),
+                                    workspace.numel() * workspace.element_size(), _stream())
+    _check(st)
+    return out.as_dict()

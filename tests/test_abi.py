@@ -126,6 +126,16 @@ def test_argument_checks_need_no_gpu(lib):
     assert lib.bload_plan_shard(p, p, p, 4, 2, 0, 2, p, p, p, nb, tot, p, 8, None) == 3      # workspace
     assert lib.bload_plan_shard(p, p, p, 0, 0, 0, 2, p, p, p, nb, tot, p, 16, None) == 0
     assert (nb.value, tot.value) == (0, 0)
+    sc = lib.bload_strategy_counts
+    sc.restype = ctypes.c_int
+    sc.argtypes = [vp, i64, i32, i32, i64, i32, vp, vp, ctypes.c_size_t, vp]
+    counts = (i64 * 6)(*([7] * 6))
+    assert sc(p, 4, 0, 0, 0, 0, counts, p, 64, None) == 1                  # t_chunk < 1
+    assert sc(p, 4, 0, 5, 0, 0, None, p, 64, None) == 1                   # nowhere to report
+    assert sc(None, 4, 0, 5, 0, 0, counts, p, 64, None) == 1
+    assert sc(p, 4, 0, 5, 0, 0, counts, p, 32, None) == 3
+    assert sc(p + 2, 4, 0, 5, 0, 0, counts, p, 64, None) == 4
+    assert sc(p, 0, 0, 5, 0, 0, counts, p, 64, None) == 0 and list(counts) == [0] * 6
     lib.bload_segment_reduce.restype = ctypes.c_int
     lib.bload_segment_reduce.argtypes = [vp, vp, vp, vp, i64, i32, i64, ctypes.c_int, ctypes.c_int,
                                          i64, vp, vp, ctypes.c_size_t, vp]
