@@ -73,6 +73,14 @@ def _load():
         lib.bload_oracle_padding.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
                                              ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
                                              ctypes.c_void_p]
+        lib.bload_oracle_segment_scan.restype = ctypes.c_int
+        lib.bload_oracle_segment_scan.argtypes = [ctypes.c_void_p] * 3 + [
+            ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_double, ctypes.c_void_p,
+            ctypes.c_void_p]
+        lib.bload_oracle_segment_scan_packed.restype = ctypes.c_int
+        lib.bload_oracle_segment_scan_packed.argtypes = [ctypes.c_void_p] * 3 + [
+            ctypes.c_int64, ctypes.c_int32, ctypes.c_int64, ctypes.c_int, ctypes.c_double,
+            ctypes.c_void_p, ctypes.c_void_p]
         lib.bload_oracle_chunk_sampling.restype = None
         lib.bload_oracle_chunk_sampling.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
                                                     ctypes.c_void_p, ctypes.c_void_p]
@@ -263,3 +271,34 @@ def chunk_sampling(lengths, t_chunk: int):
     b = np.zeros(1, dtype=np.int64)
     _load().bload_oracle_chunk_sampling(_p(L), L.shape[0], t_chunk, _p(a), _p(b))
     return int(a[0]), int(b[0])
+
+
+def segment_scan(src, src_offsets, lengths, feat_dim: int, dtype: str, decay: float):
+    """h_0 = x_0, h_t = decay * h_(t-1) + x_t inside every sequence of the ragged source.
+    Returns (h, scale), float32[sum(L), feat_dim]; scale is the same recurrence on |x|, |decay|."""
+    src = np.ascontiguousarray(src, dtype=_NP_OF[dtype])
+    so = _c(src_offsets, np.int64)
+    L = _c(lengths, np.int32)
+    total = int(so[-1]) if L.shape[0] else 0
+    out = np.full((total, feat_dim), np.nan, dtype=np.float32)
+    scale = np.full((total, feat_dim), np.nan, dtype=np.float32)
+    rc = _load().bload_oracle_segment_scan(_p(src), _p(so), _p(L), L.shape[0], feat_dim,
+                                           DTYPE_CODE[dtype], float(decay), _p(out), _p(scale))
+    if rc != 0:
+        raise ValueError("unsupported dtype")
+    return out, scale
+
+
+def segment_scan_packed(packed, reset, valid, feat_dim: int, dtype: str, decay: float):
+    """The recurrence read from packed blocks through their flags (any flags).
+    Returns (h, scale), float32[B, T, feat_dim]; invalid slots hold 0."""
+    B, T = valid.shape
+    pk = np.ascontiguousarray(packed).view(_NP_OF[dtype]).reshape(B, T, feat_dim)
+    rs, vl = _c(reset, np.uint8), _c(valid, np.uint8)
+    out = np.full((B, T, feat_dim), np.nan, dtype=np.float32)
+    scale = np.full((B, T, feat_dim), np.nan, dtype=np.float32)
+    rc = _load().bload_oracle_segment_scan_packed(_p(pk), _p(rs), _p(vl), B, T, feat_dim,
+                                                  DTYPE_CODE[dtype], float(decay), _p(out), _p(scale))
+    if rc != 0:
+        raise ValueError("unsupported dtype")
+    return out, scale

@@ -468,3 +468,76 @@ void bload_oracle_chunk_sampling(const int32_t* lengths, int64_t n, int64_t t_ch
     *samples = s;
     *deleted = d;
 }
+
+/* ------------------------------------------------------- recurrent consumer */
+
+static double oracle_element(const void* p, int dtype, int64_t e)
+{
+    if (dtype == 0) return (double)((const uint8_t*)p)[e];
+    if (dtype == 1) return bload_oracle_half_to_double(((const uint16_t*)p)[e]);
+    return (double)((const float*)p)[e];
+}
+
+/* The use the start table is made for (Methods section; the figure of the DDS model: what
+ * frame n-1 produced is part of the input of frame n, and the table says where that carried
+ * state belongs to another sequence and must be dropped).  The smallest consumer with such
+ * feedback is a first-order linear recurrence per feature,
+ *     h_0 = x_0,   h_t = decay * h_{t-1} + x_t      (t = 1 .. L-1, inside one sequence),
+ * defined here on the ragged source, so it knows nothing of blocks, plans or flags.
+ * out: float[sum(L), feat_dim] in source order, each value computed in double and rounded
+ * once.  scale (may be NULL): the same recurrence on |x| with |decay|, the magnitude a
+ * rounding-error bound is stated against.  dtype: 0 u8, 1 f16, 2 f32.  Returns 0, 1 on
+ * another dtype. */
+int bload_oracle_segment_scan(const void* src, const int64_t* src_offsets, const int32_t* lengths,
+                              int64_t n, int64_t feat_dim, int dtype, double decay, float* out,
+                              float* scale)
+{
+    if (dtype < 0 || dtype > 2) return 1;
+    double mag = decay < 0 ? -decay : decay;
+    for (int64_t i = 0; i < n; ++i) {
+        for (int64_t d = 0; d < feat_dim; ++d) {
+            double h = 0.0, s = 0.0;
+            for (int64_t t = 0; t < lengths[i]; ++t) {
+                int64_t e = (src_offsets[i] + t) * feat_dim + d;
+                double x = oracle_element(src, dtype, e);
+                if (t == 0) { h = x; s = x < 0 ? -x : x; }
+                else { h = decay * h + x; s = mag * s + (x < 0 ? -x : x); }
+                out[e] = (float)h;
+                if (scale) scale[e] = (float)s;
+            }
+        }
+    }
+    return 0;
+}
+
+/* The same recurrence read from the packed blocks through their flags (any flags): the
+ * state is dropped at a valid slot that carries a start flag, is a block's first slot or
+ * follows an invalid slot; an invalid slot yields 0.  out, scale: float[B, t_blk, feat_dim]. */
+int bload_oracle_segment_scan_packed(const void* packed, const uint8_t* reset, const uint8_t* valid,
+                                     int64_t num_blocks, int32_t t_blk, int64_t feat_dim, int dtype,
+                                     double decay, float* out, float* scale)
+{
+    if (dtype < 0 || dtype > 2) return 1;
+    double mag = decay < 0 ? -decay : decay;
+    for (int64_t b = 0; b < num_blocks; ++b) {
+        for (int64_t d = 0; d < feat_dim; ++d) {
+            double h = 0.0, s = 0.0;
+            for (int64_t t = 0; t < t_blk; ++t) {
+                int64_t slot = b * (int64_t)t_blk + t;
+                int64_t e = slot * feat_dim + d;
+                if (!valid[slot]) {
+                    out[e] = 0.0f;
+                    if (scale) scale[e] = 0.0f;
+                    continue;
+                }
+                int starts = reset[slot] != 0 || t == 0 || valid[slot - 1] == 0;
+                double x = oracle_element(packed, dtype, e);
+                if (starts) { h = x; s = x < 0 ? -x : x; }
+                else { h = decay * h + x; s = mag * s + (x < 0 ? -x : x); }
+                out[e] = (float)h;
+                if (scale) scale[e] = (float)s;
+            }
+        }
+    }
+    return 0;
+}
