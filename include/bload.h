@@ -238,6 +238,35 @@ bload_status bload_segment_reduce(const void* d_packed, const int32_t* d_seq_id,
                                   bload_dtype dtype, bload_op op, int64_t n_seq, void* d_out,
                                   void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ---------------------------------------------------------- segment scan --
+ * Methods section and the figure of the DDS model: the network feeds what it
+ * produced for frame n-1 into frame n, and the start table tells it where that
+ * carried state belongs to another sequence and has to be dropped.  This is the
+ * smallest consumer with such feedback: per feature a first-order linear
+ * recurrence along time,
+ *     h = x                   at a slot that starts a sequence
+ *     h = decay * h_prev + x  at every other valid slot
+ *     h = 0                   at a padding slot,
+ * where a slot starts a sequence exactly as for bload_segment_reduce (valid, and
+ * carrying a start flag, or first of its block, or behind an invalid slot).
+ *
+ * d_packed   in   [B, t_blk, feat_dim] of `dtype` (U8, F16 or F32; I32 is
+ *                 refused with BLOAD_EINVAL), 16-byte aligned
+ * d_reset, d_valid   in   uint8[B, t_blk]
+ * decay      in   any float
+ * d_out      out  float32[B, t_blk, feat_dim], 16-byte aligned; every element is
+ *                 written.  float32 arithmetic in time order: for the k-th frame
+ *                 of a sequence the result differs from the exact one by at most
+ *                 (2k + 1) * 2^-24 * S, S being the same recurrence run on |x|
+ *                 with |decay|.
+ * No workspace.  Asynchronous on `hip_stream`; same inputs give bit-identical
+ * outputs.
+ */
+bload_status bload_segment_scan(const void* d_packed, const uint8_t* d_reset,
+                                const uint8_t* d_valid, int64_t num_blocks, int32_t t_blk,
+                                int64_t feat_dim, bload_dtype dtype, float decay, float* d_out,
+                                void* hip_stream);
+
 /* ------------------------------------------------------- strategy counts --
  * Problem Statement and Table 1 (rows "padding amount" and "# frames deleted"):
  * what the strategies compared there cost on a given set of lengths, counted in
