@@ -5,7 +5,8 @@ A step is one pass of the whole path over one synthetic workload that is
 already resident in HBM: bload_plan (order + next-fit; --plan random-fit takes
 the paper's sampler instead), bload_pack (gather,
 zero padding, start table) and bload_segment_reduce (per-sequence reduction
-over the packed blocks).  Prints ONE JSON line.
+over the packed blocks); --scan adds bload_segment_scan (the recurrent
+consumer).  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2] [--plan next-fit]
                     [--no-cpu-baseline]
@@ -58,6 +59,9 @@ def main() -> int:
                     help="block builder: next-fit over the seeded order (default, parallel) or the "
                          "paper's sampler, uniform among the remaining sequences that fit "
                          "(bload_plan_random_fit, a sequential chain of draws)")
+    ap.add_argument("--scan", action="store_true",
+                    help="add the recurrent consumer (bload_segment_scan, decay 0.9) as a fourth phase "
+                         "of every step")
     ap.add_argument("--world", type=int, default=1,
                     help="time the share of one data-parallel worker (blocks rank mod world, "
                          "bload_plan_shard) instead of the whole workload; still one GPU")
@@ -112,7 +116,16 @@ def main() -> int:
                          dtype=torch.uint8, device=dev)
     red = torch.zeros((N, D), dtype=torch.int64 if w.dtype == "i32" else torch.float32, device=dev)
 
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    if args.scan:
+        if w.dtype == "i32":
+            print("bload_segment_scan takes u8, f16 or f32 payloads; workload 5 holds int32 tokens",
+                  file=sys.stderr)
+            return 2
+        scan_out = torch.empty((B, T, D), dtype=torch.float32, device=dev)
+        scan_ws = torch.empty(max(16, bload.bload_segment_scan_workspace_bytes(B, T, D, w.dtype)),
+                              dtype=torch.uint8, device=dev)
+
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
 
     def step(events=None):
         if events:
@@ -129,6 +142,11 @@ def main() -> int:
                                    workspace=red_ws)
         if events:
             events[3].record()
+        if args.scan:
+            bload.bload_segment_scan(packed.packed, packed.reset, packed.valid, todo.num_blocks, T, D,
+                                     w.dtype, 0.9, out=scan_out, workspace=scan_ws)
+        if events:
+            events[4].record()
 
     if args.calibrate_copy:
         a = torch.ones(1 << 28, dtype=torch.float32, device=dev)
@@ -149,8 +167,8 @@ def main() -> int:
     assert share.num_blocks == B and plan.total_frames == total_frames
     work_frames = local_frames              # valid frames one step packs
 
-    ms = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in ev])   # plan, pack, reduce
-    plan_ms, pack_ms, reduce_ms = (float(x) for x in ms.mean(axis=0))
+    ms = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(4)] for e in ev])   # plan, pack, reduce, scan
+    plan_ms, pack_ms, reduce_ms, scan_ms = (float(x) for x in ms.mean(axis=0))
     ms_per_step = elapsed / args.steps * 1e3
 
     slots = B * T
@@ -223,6 +241,13 @@ def main() -> int:
         },
     }
 
+    if args.scan:
+        bytes_scan = work_frames * F + slots * D * 4 + 2 * slots
+        result["phases_ms"]["segment_scan"] = scan_ms
+        result["segment_scan"] = {"algorithmic_GBps": bytes_scan / (scan_ms * 1e-3) / 1e9,
+                                  "algorithmic_bytes_per_launch": bytes_scan, "decay": 0.9}
+        result["config"]["workload"] += ", with the recurrent consumer"
+
     if not args.no_cpu_baseline and not sharded:
         import oracle
         # the oracle as it stands, one thread: order + plan + pack + reduce of the same workload
@@ -242,7 +267,8 @@ def main() -> int:
             "cores": 1,
             "kind": "oracle",
             "sample": f"the whole workload once ({N} sequences, {total_frames} frames): "
-                      f"plan {c1 - c0:.3f} s, pack {c2 - c1:.3f} s, reduce {c3 - c2:.3f} s",
+                      f"plan {c1 - c0:.3f} s, pack {c2 - c1:.3f} s, reduce {c3 - c2:.3f} s"
+                      + (" (the recurrent consumer is not part of the CPU leg)" if args.scan else ""),
             "host_cores_visible": os.cpu_count(),
         }
     print(json.dumps(result))

@@ -255,17 +255,23 @@ bload_status bload_segment_reduce(const void* d_packed, const int32_t* d_seq_id,
  * d_reset, d_valid   in   uint8[B, t_blk]
  * decay      in   any float
  * d_out      out  float32[B, t_blk, feat_dim], 16-byte aligned; every element is
- *                 written.  float32 arithmetic in time order: for the k-th frame
- *                 of a sequence the result differs from the exact one by at most
- *                 (2k + 1) * 2^-24 * S, S being the same recurrence run on |x|
- *                 with |decay|.
- * No workspace.  Asynchronous on `hip_stream`; same inputs give bit-identical
- * outputs.
+ *                 written.  float32 arithmetic in time order inside chunks of time;
+ *                 a sequence that crosses a chunk border receives the state in
+ *                 front of the chunk as decay^chunk * (state one chunk earlier) +
+ *                 (the chunk's own part).  For the k-th frame of a sequence the
+ *                 result differs from the exact one by at most (3k + 4) * 2^-24 * S,
+ *                 S being the same recurrence run on |x| with |decay|.
+ * d_workspace     device scratch of >= bload_segment_scan_workspace_bytes(...)
+ *                 bytes, 16-byte aligned (may be NULL when that is 0).
+ * Asynchronous on `hip_stream`; same inputs give bit-identical outputs.
  */
+size_t bload_segment_scan_workspace_bytes(int64_t num_blocks, int32_t t_blk, int64_t feat_dim,
+                                          bload_dtype dtype);
+
 bload_status bload_segment_scan(const void* d_packed, const uint8_t* d_reset,
                                 const uint8_t* d_valid, int64_t num_blocks, int32_t t_blk,
                                 int64_t feat_dim, bload_dtype dtype, float decay, float* d_out,
-                                void* hip_stream);
+                                void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
 /* ------------------------------------------------------- strategy counts --
  * Problem Statement and Table 1 (rows "padding amount" and "# frames deleted"):

@@ -71,7 +71,9 @@ _lib.bload_strategy_counts.argtypes = [_vp, _i64, _i32, _i32, _i64, _i32,
                                        ctypes.POINTER(StrategyCounts), _vp, _sz, _vp]
 _lib.bload_segment_scan.restype = ctypes.c_int
 _lib.bload_segment_scan.argtypes = [_vp, _vp, _vp, _i64, _i32, _i64, ctypes.c_int, ctypes.c_float, _vp,
-                                    _vp]
+                                    _vp, _sz, _vp]
+_lib.bload_segment_scan_workspace_bytes.restype = _sz
+_lib.bload_segment_scan_workspace_bytes.argtypes = [_i64, _i32, _i64, ctypes.c_int]
 _lib.bload_segment_reduce_workspace_bytes.restype = _sz
 _lib.bload_segment_reduce_workspace_bytes.argtypes = [_i64, _i32, _i64, ctypes.c_int]
 _lib.bload_segment_reduce.restype = ctypes.c_int
@@ -305,15 +307,24 @@ def bload_strategy_counts(lengths: torch.Tensor, t_chunk: int, t_max: int = 0, n
     return out.as_dict()
 
 
+def bload_segment_scan_workspace_bytes(num_blocks: int, t_blk: int, feat_dim: int, dtype: str) -> int:
+    return int(_lib.bload_segment_scan_workspace_bytes(num_blocks, t_blk, feat_dim, DTYPES[dtype]))
+
+
 def bload_segment_scan(packed: torch.Tensor, reset: torch.Tensor, valid: torch.Tensor, num_blocks: int,
                        t_blk: int, feat_dim: int, dtype: str, decay: float,
-                       out: torch.Tensor | None = None) -> torch.Tensor:
+                       out: torch.Tensor | None = None,
+                       workspace: torch.Tensor | None = None) -> torch.Tensor:
     """h = x at sequence starts, decay * h_prev + x elsewhere, 0 on padding: float32
     [num_blocks, t_blk, feat_dim].  Asynchronous on the current stream."""
     if out is None:
         out = torch.empty((num_blocks, t_blk, feat_dim), dtype=torch.float32, device=packed.device)
+    if workspace is None:
+        need = bload_segment_scan_workspace_bytes(num_blocks, t_blk, feat_dim, dtype) if dtype != "i32" else 0
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=packed.device)
     st = _lib.bload_segment_scan(_ptr(packed), _ptr(reset, torch.uint8), _ptr(valid, torch.uint8),
                                  num_blocks, t_blk, feat_dim, DTYPES[dtype], float(decay),
-                                 _ptr(out, torch.float32), _stream())
+                                 _ptr(out, torch.float32), _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream())
     _check(st)
     return out

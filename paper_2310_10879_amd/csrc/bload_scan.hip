@@ -5,30 +5,42 @@
 // padding slots yield 0.  Output float32 [B, t_blk, feat_dim].
 //
 // HBM bound, and write heavy (4 output bytes per element).  The recurrence runs along time,
-// so parallelism comes from blocks, features and *pieces of time that need no carry-in*:
-// a slot that is padding or starts a sequence ("boundary") depends on nothing before it.
-// Time is cut into chunks; the worker of a chunk owns the slots from the chunk's first
-// boundary up to the first boundary at or behind the chunk's end.  Every slot has exactly
-// one owner, is read once and written once, and no worker ever waits for another.
+// so parallelism comes from blocks, features and chunks of time.  A slot that is padding or
+// starts a sequence ("boundary") depends on nothing before it; only a sequence that runs
+// across a chunk border hands a state on.  Three kernels, all deterministic:
+//   scan_tail_kernel   per chunk (but the block's last): the state it would hand on if it
+//                      received none - the recurrence from the chunk's last boundary (or its
+//                      first slot) to its end - and whether it holds a boundary at all
+//   scan_chain_kernel  per block and feature, along the chunks: state handed to chunk c+1 =
+//                      the tail state of chunk c, plus decay^chunk * (state handed to c) when
+//                      chunk c holds no boundary
+//   scan_apply_kernel  per chunk: the recurrence over its own slots from the state handed in
+// Every slot is read and written once by scan_apply; scan_tail re-reads only the open ends
+// of the chunks.  With one chunk per block only scan_apply runs.
 //
 // A row of lanes (16 input bytes per lane where the frame allows it, taken as quads of 4
 // elements laid out so that every load and store instruction of the row is contiguous; else
 // one element per lane) covers the features; a wavefront holds 64 / row-width rows, each on
-// a chunk of its own.  All loads of a pass are unconditional and issued together.
+// a chunk of its own.  All loads of a step are unconditional and issued together.
 #include "bload_common.hpp"
 
 #include <hip/hip_fp16.h>
+#include <math.h>
 
 namespace bload {
 
 constexpr int kScanBatch = 8;          // slots per step and row: their loads are in flight together
+constexpr uint32_t kScanAll = (1u << kScanBatch) - 1u;
+static_assert(kScanBatch % 8 == 0 && kScanBatch <= 24, "flags come eight to a load");
 
 struct ScanArgs {
     const uint8_t* packed;
     const uint8_t* reset;
     const uint8_t* valid;
     float* out;
-    int64_t items;                     // num_blocks * chunks_per_block
+    float* carry;                      // [B, chunks_per_block - 1, feat_dim]: tail states, then states handed on
+    uint8_t* has_boundary;             // [B, chunks_per_block - 1]
+    int64_t num_blocks;
     int32_t t_blk;
     int32_t feat_dim;
     int32_t chunk;                     // slots per chunk
@@ -38,6 +50,7 @@ struct ScanArgs {
     int32_t n_vec;                     // quads (4 elements) of a frame, or elements where a frame
                                        // is not a whole number of 16-byte pieces
     float decay;
+    float decay_chunk;                 // decay ^ chunk
 };
 
 template <typename ElemT> struct ScanElem;
@@ -86,129 +99,223 @@ __device__ __forceinline__ uint32_t scan_flags8(const uint8_t* __restrict__ plan
     return (uint32_t)(((top >> 7) * 0x0102040810204080ull) >> 56);
 }
 
-// A lane holds QUADS quads of a frame: quad g of lane r in a row of `row_lanes` lanes is
-// quad number tile_base + g * row_lanes + r, so that each load and each store instruction of
-// a row covers one contiguous stretch of the frame.
-template <typename ElemT, int QUADS, bool VEC>
-__global__ __launch_bounds__(kThreads) void scan_kernel(ScanArgs a)
+// Flags of the kScanBatch slots from t on, and which of them are boundaries: padding, a start
+// flag, the block's first slot, or the slot after padding.  `before`: was slot t - 1 valid.
+struct ScanFlags { uint32_t valid, boundary; };
+__device__ __forceinline__ ScanFlags scan_flags(const uint8_t* __restrict__ valid,
+                                                const uint8_t* __restrict__ reset, int32_t t, int32_t T,
+                                                uint32_t before)
 {
-    constexpr int EPL = VEC ? QUADS * 4 : 1;             // elements per lane
-    const int lane = lane_id();
-    const int rows_per_wave = kWave / a.row_lanes;
-    const int64_t wave = (int64_t)blockIdx.x * (kThreads / kWave) + wave_id();
-    const int32_t feat_tile = (int32_t)(wave % a.feat_tiles);
-    const int64_t item = (wave / a.feat_tiles) * rows_per_wave + lane / a.row_lanes;
-    const int32_t r = lane & (a.row_lanes - 1);
-    // first quad (VEC) or element of the lane
-    const int32_t first = VEC ? feat_tile * a.row_lanes * QUADS + r : feat_tile * a.row_lanes + r;
+    const uint32_t in_range = T - t >= kScanBatch ? kScanAll : (1u << (T - t)) - 1u;
+    uint32_t vm = 0, rm = 0;
+#pragma unroll
+    for (int part = 0; part < kScanBatch; part += 8) {
+        if (part == 0 || t + part < T) {
+            vm |= scan_flags8(valid, t + part, T) << part;
+            rm |= scan_flags8(reset, t + part, T) << part;
+        }
+    }
+    const uint32_t prev_valid = (vm << 1) | before;
+    return ScanFlags{vm, in_range & (~vm | rm | ~prev_valid | (t == 0 ? 1u : 0u))};
+}
 
-    bool done = item >= a.items || first >= a.n_vec;
-    const int64_t block = done ? 0 : item / a.chunks_per_block;
-    const int32_t chunk = done ? 0 : (int32_t)(item - block * a.chunks_per_block);
-    const int64_t slot0 = block * a.t_blk;                     // first slot of the block
-    const int32_t T = a.t_blk;
-    int32_t t = chunk * a.chunk;
-    const int32_t t_end = min(T, t + a.chunk);
-    if (t >= T) done = true;
+// What a lane works on.  It holds QUADS quads of a frame: quad g of lane r in a row of
+// `row_lanes` lanes is quad number tile_base + g * row_lanes + r, so that each load and each
+// store instruction of a row covers one contiguous stretch of the frame.
+template <typename ElemT, int QUADS, bool VEC>
+struct ScanLane {
+    static constexpr int EPL = VEC ? QUADS * 4 : 1;      // elements per lane
+    bool idle;
+    int64_t block;
+    int32_t chunk;
+    int32_t t0, t1;                    // the chunk's slots inside the block
+    int64_t first_elem;                // first element of the lane inside a frame
+    int32_t quad_stride;               // elements between the lane's quads
+    bool quad_on[QUADS];
+
+    __device__ __forceinline__ ScanLane(const ScanArgs& a, int32_t chunks_used)
+    {
+        const int lane = lane_id();
+        const int rows_per_wave = kWave / a.row_lanes;
+        const int64_t wave = (int64_t)xcd_contiguous(blockIdx.x, gridDim.x) * (kThreads / kWave) + wave_id();
+        const int32_t feat_tile = (int32_t)(wave % a.feat_tiles);
+        const int64_t item = (wave / a.feat_tiles) * rows_per_wave + lane / a.row_lanes;
+        const int32_t r = lane & (a.row_lanes - 1);
+        const int32_t first = VEC ? feat_tile * a.row_lanes * QUADS + r : feat_tile * a.row_lanes + r;
+        idle = item >= a.num_blocks * chunks_used || first >= a.n_vec;
+        block = idle ? 0 : item / chunks_used;
+        chunk = idle ? 0 : (int32_t)(item - block * chunks_used);
+        t0 = chunk * a.chunk;
+        t1 = min(a.t_blk, t0 + a.chunk);
+        if (t0 >= a.t_blk) idle = true;
+        first_elem = (int64_t)first * (VEC ? 4 : 1);
+        quad_stride = a.row_lanes * 4;
+#pragma unroll
+        for (int g = 0; g < QUADS; ++g) quad_on[g] = !VEC || first + g * a.row_lanes < a.n_vec;
+    }
+
+    // kScanBatch slots from t on (slots behind the block's end re-read its last slot): the
+    // recurrence goes on in h; `keep` slots are handed to `emit(u, g, quad)`.
+    template <typename Emit>
+    __device__ __forceinline__ void step(const ScanArgs& a, const uint8_t* __restrict__ frames, int32_t t,
+                                         ScanFlags f, float (&h)[EPL], int keep, Emit emit) const
+    {
+        const int64_t frame_bytes = (int64_t)a.feat_dim * (int64_t)sizeof(ElemT);
+        const uint8_t* src = frames + first_elem * (int64_t)sizeof(ElemT);
+        if (VEC) {
+            ScanQuad<ElemT> x[kScanBatch][QUADS];
+#pragma unroll
+            for (int u = 0; u < kScanBatch; ++u) {
+                const uint8_t* frame = src + (int64_t)min(t + u, a.t_blk - 1) * frame_bytes;
+#pragma unroll
+                for (int g = 0; g < QUADS; ++g) {
+                    const int64_t at = quad_on[g] ? (int64_t)g * quad_stride * (int64_t)sizeof(ElemT) : 0;
+                    x[u][g].bits = __builtin_nontemporal_load(
+                        reinterpret_cast<const typename ScanBits<sizeof(ElemT) * 4>::T*>(frame + at));
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kScanBatch; ++u) {
+                const bool is_valid = (f.valid >> u) & 1u, starts = (f.boundary >> u) & 1u;
+#pragma unroll
+                for (int g = 0; g < QUADS; ++g) {
+                    float4v o;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float xv = is_valid ? ScanElem<ElemT>::get(x[u][g].e[j]) : 0.0f;
+                        h[g * 4 + j] = (starts ? 0.0f : a.decay * h[g * 4 + j]) + xv;
+                        o[j] = h[g * 4 + j];
+                    }
+                    if (u < keep && quad_on[g]) emit(u, g, o);
+                }
+            }
+        } else {
+            ElemT x[kScanBatch];
+#pragma unroll
+            for (int u = 0; u < kScanBatch; ++u)
+                x[u] = *reinterpret_cast<const ElemT*>(src + (int64_t)min(t + u, a.t_blk - 1) * frame_bytes);
+#pragma unroll
+            for (int u = 0; u < kScanBatch; ++u) {
+                const bool is_valid = (f.valid >> u) & 1u, starts = (f.boundary >> u) & 1u;
+                const float xv = is_valid ? ScanElem<ElemT>::get(x[u]) : 0.0f;
+                h[0] = (starts ? 0.0f : a.decay * h[0]) + xv;
+                float4v o = {h[0], 0.0f, 0.0f, 0.0f};
+                if (u < keep) emit(u, 0, o);
+            }
+        }
+    }
+};
+
+// The state a chunk hands on when it receives none, and whether it holds a boundary.
+template <typename ElemT, int QUADS, bool VEC>
+__global__ __launch_bounds__(kThreads) void scan_tail_kernel(ScanArgs a)
+{
+    typedef ScanLane<ElemT, QUADS, VEC> Lane;
+    const Lane me(a, a.chunks_per_block - 1);                 // the block's last chunk hands nothing on
+    if (me.idle) return;
+    const int64_t slot0 = me.block * a.t_blk;
     const uint8_t* __restrict__ valid = a.valid + slot0;
     const uint8_t* __restrict__ reset = a.reset + slot0;
-    const int64_t frame_bytes = (int64_t)a.feat_dim * (int64_t)sizeof(ElemT);
-    const uint8_t* src = a.packed + slot0 * frame_bytes + (int64_t)first * (int64_t)(VEC ? 4 : 1) * (int64_t)sizeof(ElemT);
-    float* dst = a.out + slot0 * (int64_t)a.feat_dim + (int64_t)first * (VEC ? 4 : 1);
-    bool quad_on[QUADS];
+
+    // the chunk's last boundary
+    int32_t last = -1;
+    uint32_t before = me.t0 > 0 ? (valid[me.t0 - 1] != 0) : 0u;
+    for (int32_t t = me.t0; t < me.t1; t += kScanBatch) {
+        const ScanFlags f = scan_flags(valid, reset, t, a.t_blk, before);
+        const int n = min(kScanBatch, me.t1 - t);
+        const uint32_t mine = f.boundary & ((1u << n) - 1u);
+        if (mine) last = t + 31 - __builtin_clz(mine);
+        before = (f.valid >> (n - 1)) & 1u;
+    }
+
+    // the recurrence from there (from the chunk's first slot if there is none) to the chunk's end
+    const int32_t from = last >= 0 ? last : me.t0;
+    float h[Lane::EPL];
 #pragma unroll
-    for (int g = 0; g < QUADS; ++g) quad_on[g] = !VEC || first + g * a.row_lanes < a.n_vec;
+    for (int k = 0; k < Lane::EPL; ++k) h[k] = 0.0f;
+    float* carry = a.carry + (me.block * (a.chunks_per_block - 1) + me.chunk) * (int64_t)a.feat_dim + me.first_elem;
+    before = from > 0 ? (valid[from - 1] != 0) : 0u;
+    for (int32_t t = from; t < me.t1; t += kScanBatch) {
+        const ScanFlags f = scan_flags(valid, reset, t, a.t_blk, before);
+        const int n = min(kScanBatch, me.t1 - t);
+        const bool ends = t + n >= me.t1;
+        me.step(a, a.packed + slot0 * a.feat_dim * (int64_t)sizeof(ElemT), t, f, h, n,
+                [&](int u, int g, float4v o) {
+                    if (ends && u == n - 1) {
+                        if (VEC) *reinterpret_cast<float4v*>(carry + g * me.quad_stride) = o;
+                        else carry[0] = o[0];
+                    }
+                });
+        before = (f.valid >> (n - 1)) & 1u;
+    }
+    if (me.first_elem == 0) a.has_boundary[me.block * (a.chunks_per_block - 1) + me.chunk] = last >= 0;
+}
 
-    bool owning = false;               // past the chunk's first boundary
-    uint32_t before = (!done && t > 0) ? (valid[t - 1] != 0) : 0u;    // was the slot in front valid
-    float h[EPL];
+// Along the chunks of a block: what chunk c + 1 is handed = the tail state of chunk c, plus
+// decay^chunk times what chunk c was handed if chunk c holds no boundary.  In place.
+__global__ __launch_bounds__(kThreads) void scan_chain_kernel(ScanArgs a)
+{
+    const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= a.num_blocks * a.feat_dim) return;
+    const int64_t block = idx / a.feat_dim, d = idx - block * a.feat_dim;
+    const int32_t links = a.chunks_per_block - 1;
+    float handed = 0.0f;
+    for (int32_t c = 0; c < links; ++c) {
+        const int64_t at = (block * links + c) * (int64_t)a.feat_dim + d;
+        const float tail = a.carry[at];
+        handed = a.has_boundary[block * links + c] ? tail : a.decay_chunk * handed + tail;
+        a.carry[at] = handed;
+    }
+}
+
+// The recurrence over a chunk's own slots, from the state handed in.
+template <typename ElemT, int QUADS, bool VEC>
+__global__ __launch_bounds__(kThreads) void scan_apply_kernel(ScanArgs a)
+{
+    typedef ScanLane<ElemT, QUADS, VEC> Lane;
+    const Lane me(a, a.chunks_per_block);
+    if (me.idle) return;
+    const int64_t slot0 = me.block * a.t_blk;
+    const uint8_t* __restrict__ valid = a.valid + slot0;
+    const uint8_t* __restrict__ reset = a.reset + slot0;
+    float h[Lane::EPL];
 #pragma unroll
-    for (int k = 0; k < EPL; ++k) h[k] = 0.0f;
-
-    // Every pass moves each unfinished row forward (t grows, or the row starts owning), and a
-    // row is finished at the latest when t reaches the block's end.
-    while (__any(!done)) {
-        if (!done) {
-            const uint32_t in_range = T - t >= kScanBatch ? 0xffu : (1u << (T - t)) - 1u;
-            const uint32_t vm = scan_flags8(valid, t, T);
-            const uint32_t rm = scan_flags8(reset, t, T);
-            // boundary: padding, a start flag, the block's first slot, or the slot after padding
-            const uint32_t prev_valid = (vm << 1) | before;
-            const uint32_t boundary = in_range & (~vm | rm | ~prev_valid | (t == 0 ? 1u : 0u));
-            // bit u set iff slot t + u lies at or behind the chunk's end
-            const int32_t to_end = t_end - t;
-            const uint32_t behind = to_end >= kScanBatch ? 0u : (to_end <= 0 ? ~0u : ~0u << to_end);
-
-            int advance;
-            if (!owning) {
-                const uint32_t mine = boundary & ~behind;
-                if (mine) {
-                    advance = __builtin_ctz(mine);
-                    owning = true;
-                } else {
-                    advance = kScanBatch;
-                    if (t + advance >= t_end) done = true;    // the chunk holds no boundary: nothing to own
-                }
-            } else {
-                const uint32_t stop = boundary & behind;
-                const int n = stop ? __builtin_ctz(stop) : min(kScanBatch, T - t);
-                // all loads of the pass first, none of them conditional (slots behind the
-                // block's end re-read its last slot and are not used)
+    for (int k = 0; k < Lane::EPL; ++k) h[k] = 0.0f;
+    if (me.chunk > 0) {
+        const float* handed = a.carry + (me.block * (a.chunks_per_block - 1) + me.chunk - 1) * (int64_t)a.feat_dim +
+                              me.first_elem;
+#pragma unroll
+        for (int g = 0; g < QUADS; ++g) {
+            if (me.quad_on[g]) {
                 if (VEC) {
-                    ScanQuad<ElemT> x[kScanBatch][QUADS];
+                    const float4v v = *reinterpret_cast<const float4v*>(handed + g * me.quad_stride);
 #pragma unroll
-                    for (int u = 0; u < kScanBatch; ++u) {
-                        const uint8_t* frame = src + (int64_t)min(t + u, T - 1) * frame_bytes;
-#pragma unroll
-                        for (int g = 0; g < QUADS; ++g) {
-                            const int64_t at = quad_on[g] ? (int64_t)g * a.row_lanes * 4 * (int64_t)sizeof(ElemT) : 0;
-                            x[u][g].bits = __builtin_nontemporal_load(
-                                reinterpret_cast<const typename ScanBits<sizeof(ElemT) * 4>::T*>(frame + at));
-                        }
-                    }
-#pragma unroll
-                    for (int u = 0; u < kScanBatch; ++u) {
-                        const bool is_valid = (vm >> u) & 1u, starts = (boundary >> u) & 1u;
-#pragma unroll
-                        for (int g = 0; g < QUADS; ++g) {
-                            float4v o;
-#pragma unroll
-                            for (int j = 0; j < 4; ++j) {
-                                const float xv = is_valid ? ScanElem<ElemT>::get(x[u][g].e[j]) : 0.0f;
-                                h[g * 4 + j] = (starts ? 0.0f : a.decay * h[g * 4 + j]) + xv;
-                                o[j] = h[g * 4 + j];
-                            }
-                            if (u < n && quad_on[g])
-                                __builtin_nontemporal_store(
-                                    o, reinterpret_cast<float4v*>(dst + (int64_t)(t + u) * a.feat_dim +
-                                                                  (int64_t)g * a.row_lanes * 4));
-                        }
-                    }
+                    for (int j = 0; j < 4; ++j) h[g * 4 + j] = v[j];
                 } else {
-                    ElemT x[kScanBatch];
-#pragma unroll
-                    for (int u = 0; u < kScanBatch; ++u)
-                        x[u] = *reinterpret_cast<const ElemT*>(src + (int64_t)min(t + u, T - 1) * frame_bytes);
-#pragma unroll
-                    for (int u = 0; u < kScanBatch; ++u) {
-                        const bool is_valid = (vm >> u) & 1u, starts = (boundary >> u) & 1u;
-                        const float xv = is_valid ? ScanElem<ElemT>::get(x[u]) : 0.0f;
-                        h[0] = (starts ? 0.0f : a.decay * h[0]) + xv;
-                        if (u < n) __builtin_nontemporal_store(h[0], dst + (int64_t)(t + u) * a.feat_dim);
-                    }
+                    h[0] = handed[0];
                 }
-                advance = n;
-                if (stop || t + n >= T) done = true;
             }
-            if (advance > 0) before = (vm >> (advance - 1)) & 1u;
-            t += advance;
         }
+    }
+    float* dst = a.out + slot0 * (int64_t)a.feat_dim + me.first_elem;
+    uint32_t before = me.t0 > 0 ? (valid[me.t0 - 1] != 0) : 0u;
+    for (int32_t t = me.t0; t < me.t1; t += kScanBatch) {
+        const ScanFlags f = scan_flags(valid, reset, t, a.t_blk, before);
+        const int n = min(kScanBatch, me.t1 - t);
+        me.step(a, a.packed + slot0 * a.feat_dim * (int64_t)sizeof(ElemT), t, f, h, n,
+                [&](int u, int g, float4v o) {
+                    float* to = dst + (int64_t)(t + u) * a.feat_dim;
+                    if (VEC) __builtin_nontemporal_store(o, reinterpret_cast<float4v*>(to + g * me.quad_stride));
+                    else __builtin_nontemporal_store(o[0], to);
+                });
+        before = (f.valid >> (n - 1)) & 1u;
     }
 }
 
 struct ScanPlan {
     int32_t epv, n_vec, row_lanes, feat_tiles, chunk, chunks_per_block;
-    int64_t waves;
+    int64_t rows_per_wave;
+    size_t carry_bytes, bytes;         // workspace: the states handed on, then the boundary marks
 };
 
 static ScanPlan scan_plan(int64_t num_blocks, int32_t t_blk, int64_t feat_dim, size_t elem)
@@ -221,36 +328,63 @@ static ScanPlan scan_plan(int64_t num_blocks, int32_t t_blk, int64_t feat_dim, s
     p.row_lanes = 1;
     while (p.row_lanes < kWave && p.row_lanes * per_lane < p.n_vec) p.row_lanes *= 2;
     p.feat_tiles = (int32_t)ceil_div(p.n_vec, p.row_lanes * per_lane);
-    const int64_t rows_per_wave = kWave / p.row_lanes;
-    // enough wavefronts to fill the chip several times over, chunks not shorter than 32 slots
-    const int64_t want_waves = 16384;
-    int64_t chunks = ceil_div(want_waves * rows_per_wave, num_blocks * p.feat_tiles);
-    const int64_t most = t_blk / 32 > 1 ? t_blk / 32 : 1;
+    p.rows_per_wave = kWave / p.row_lanes;
+    // enough wavefronts to fill the chip several times over, chunks not shorter than 64 slots
+    const int64_t want_waves = 6144;
+    int64_t chunks = ceil_div(want_waves * p.rows_per_wave, (num_blocks > 0 ? num_blocks : 1) * p.feat_tiles);
+    const int64_t most = t_blk / 64 > 1 ? t_blk / 64 : 1;
     if (chunks > most) chunks = most;
     if (chunks < 1) chunks = 1;
     p.chunk = (int32_t)round_up((size_t)ceil_div(t_blk, chunks), kScanBatch);
     p.chunks_per_block = (int32_t)ceil_div(t_blk, p.chunk);
-    p.waves = ceil_div(num_blocks * p.chunks_per_block, rows_per_wave) * p.feat_tiles;
+    const size_t links = (size_t)(num_blocks > 0 ? num_blocks : 0) * (size_t)(p.chunks_per_block - 1);
+    p.carry_bytes = round_up(links * (size_t)feat_dim * sizeof(float), 16);
+    p.bytes = p.carry_bytes + round_up(links, 16);
     return p;
+}
+
+static size_t scan_elem_bytes(bload_dtype dtype)
+{
+    return dtype == BLOAD_U8 ? 1 : (dtype == BLOAD_F16 ? 2 : 4);
 }
 
 template <typename ElemT>
 static void scan_launch(const ScanArgs& a, const ScanPlan& p, hipStream_t stream)
 {
-    const dim3 grid((uint32_t)ceil_div(p.waves, kThreads / kWave)), block(kThreads);
     constexpr int kQuads = 4 / (int)sizeof(ElemT);           // quads in 16 input bytes
-    if (p.epv > 1) hipLaunchKernelGGL((scan_kernel<ElemT, kQuads, true>), grid, block, 0, stream, a);
-    else hipLaunchKernelGGL((scan_kernel<ElemT, 1, false>), grid, block, 0, stream, a);
+    const dim3 block(kThreads);
+    const int waves_per_group = kThreads / kWave;
+    if (p.chunks_per_block > 1) {
+        const int64_t waves = ceil_div(a.num_blocks * (p.chunks_per_block - 1), p.rows_per_wave) * p.feat_tiles;
+        const dim3 grid((uint32_t)ceil_div(waves, waves_per_group));
+        if (p.epv > 1) hipLaunchKernelGGL((scan_tail_kernel<ElemT, kQuads, true>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((scan_tail_kernel<ElemT, 1, false>), grid, block, 0, stream, a);
+        hipLaunchKernelGGL(scan_chain_kernel, dim3((uint32_t)ceil_div(a.num_blocks * a.feat_dim, kThreads)),
+                           block, 0, stream, a);
+    }
+    const int64_t waves = ceil_div(a.num_blocks * p.chunks_per_block, p.rows_per_wave) * p.feat_tiles;
+    const dim3 grid((uint32_t)ceil_div(waves, waves_per_group));
+    if (p.epv > 1) hipLaunchKernelGGL((scan_apply_kernel<ElemT, kQuads, true>), grid, block, 0, stream, a);
+    else hipLaunchKernelGGL((scan_apply_kernel<ElemT, 1, false>), grid, block, 0, stream, a);
 }
 
 }  // namespace bload
 
 using namespace bload;
 
+extern "C" size_t bload_segment_scan_workspace_bytes(int64_t num_blocks, int32_t t_blk, int64_t feat_dim,
+                                                     bload_dtype dtype)
+{
+    if (num_blocks < 0 || t_blk < 1 || feat_dim < 1 || feat_dim > (1 << 28)) return 0;
+    if (dtype != BLOAD_U8 && dtype != BLOAD_F16 && dtype != BLOAD_F32) return 0;
+    return scan_plan(num_blocks, t_blk, feat_dim, scan_elem_bytes(dtype)).bytes;
+}
+
 extern "C" bload_status bload_segment_scan(const void* d_packed, const uint8_t* d_reset,
                                            const uint8_t* d_valid, int64_t num_blocks, int32_t t_blk,
                                            int64_t feat_dim, bload_dtype dtype, float decay,
-                                           float* d_out, void* hip_stream)
+                                           float* d_out, void* d_workspace, size_t workspace_bytes,
+                                           void* hip_stream)
 {
     if (num_blocks < 0 || t_blk < 1 || feat_dim < 1 || feat_dim > (1 << 28)) return BLOAD_EINVAL;
     if (dtype != BLOAD_U8 && dtype != BLOAD_F16 && dtype != BLOAD_F32) return BLOAD_EINVAL;
@@ -258,16 +392,25 @@ extern "C" bload_status bload_segment_scan(const void* d_packed, const uint8_t* 
     if (!d_packed || !d_reset || !d_valid || !d_out) return BLOAD_EINVAL;
     if (!aligned_to(d_packed, 16) || !aligned_to(d_out, 16)) return BLOAD_EALIGN;
     if (num_blocks * (int64_t)t_blk >= ((int64_t)1 << 40)) return BLOAD_EOVERFLOW;
-    const size_t elem = dtype == BLOAD_U8 ? 1 : (dtype == BLOAD_F16 ? 2 : 4);
-    const ScanPlan p = scan_plan(num_blocks, t_blk, feat_dim, elem);
-    if (ceil_div(p.waves, kThreads / kWave) > 0x7fffffffLL) return BLOAD_EOVERFLOW;
+    const ScanPlan p = scan_plan(num_blocks, t_blk, feat_dim, scan_elem_bytes(dtype));
+    if (p.bytes > 0) {
+        if (!d_workspace) return BLOAD_EINVAL;
+        if (!aligned_to(d_workspace, 16)) return BLOAD_EALIGN;
+        if (workspace_bytes < p.bytes) return BLOAD_EWORKSPACE;
+    }
+    const int64_t most_waves = ceil_div(num_blocks * p.chunks_per_block, p.rows_per_wave) * p.feat_tiles;
+    if (ceil_div(most_waves, kThreads / kWave) > 0x7fffffffLL ||
+        ceil_div(num_blocks * feat_dim, kThreads) > 0x7fffffffLL)
+        return BLOAD_EOVERFLOW;
 
     ScanArgs a{};
     a.packed = static_cast<const uint8_t*>(d_packed);
     a.reset = d_reset;
     a.valid = d_valid;
     a.out = d_out;
-    a.items = num_blocks * p.chunks_per_block;
+    a.carry = static_cast<float*>(d_workspace);
+    a.has_boundary = static_cast<uint8_t*>(d_workspace) + p.carry_bytes;
+    a.num_blocks = num_blocks;
     a.t_blk = t_blk;
     a.feat_dim = (int32_t)feat_dim;
     a.chunk = p.chunk;
@@ -276,6 +419,7 @@ extern "C" bload_status bload_segment_scan(const void* d_packed, const uint8_t* 
     a.feat_tiles = p.feat_tiles;
     a.n_vec = p.n_vec;
     a.decay = decay;
+    a.decay_chunk = (float)pow((double)decay, (double)p.chunk);
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (dtype == BLOAD_U8) scan_launch<uint8_t>(a, p, stream);

@@ -128,14 +128,20 @@ def test_argument_checks_need_no_gpu(lib):
     assert (nb.value, tot.value) == (0, 0)
     scan = lib.bload_segment_scan
     scan.restype = ctypes.c_int
-    scan.argtypes = [vp, vp, vp, i64, i32, i64, ctypes.c_int, ctypes.c_float, vp, vp]
-    assert scan(p, p, p, 2, 8, 4, 3, 0.5, p, None) == 1                   # int32 payload
-    assert scan(p, p, p, 2, 0, 4, 2, 0.5, p, None) == 1
-    assert scan(p, p, p, 2, 8, 0, 2, 0.5, p, None) == 1
-    assert scan(p, None, p, 2, 8, 4, 2, 0.5, p, None) == 1
-    assert scan(p + 4, p, p, 2, 8, 4, 2, 0.5, p, None) == 4
-    assert scan(p, p, p, 2, 8, 4, 2, 0.5, p + 8, None) == 4
-    assert scan(p, p, p, 0, 8, 4, 2, 0.5, p, None) == 0
+    scan.argtypes = [vp, vp, vp, i64, i32, i64, ctypes.c_int, ctypes.c_float, vp, vp, ctypes.c_size_t, vp]
+    assert scan(p, p, p, 2, 8, 4, 3, 0.5, p, p, 1 << 20, None) == 1       # int32 payload
+    assert scan(p, p, p, 2, 0, 4, 2, 0.5, p, p, 1 << 20, None) == 1
+    assert scan(p, p, p, 2, 8, 0, 2, 0.5, p, p, 1 << 20, None) == 1
+    assert scan(p, None, p, 2, 8, 4, 2, 0.5, p, p, 1 << 20, None) == 1
+    assert scan(p + 4, p, p, 2, 8, 4, 2, 0.5, p, p, 1 << 20, None) == 4
+    assert scan(p, p, p, 2, 8, 4, 2, 0.5, p + 8, p, 1 << 20, None) == 4
+    assert scan(p, p, p, 2, 3000, 4, 2, 0.5, p, p, 16, None) == 3         # chunks need their states
+    assert scan(p, p, p, 0, 8, 4, 2, 0.5, p, p, 0, None) == 0
+    sw = lib.bload_segment_scan_workspace_bytes
+    sw.restype = ctypes.c_size_t
+    sw.argtypes = [i64, i32, i64, ctypes.c_int]
+    assert sw(2, 8, 4, 2) == 0 and sw(2, 8, 4, 3) == 0                    # one chunk: nothing handed on
+    assert sw(2, 3000, 4, 2) >= 2 * 4 * 4 and sw(2, 3000, 4, 2) % 16 == 0
     sc = lib.bload_strategy_counts
     sc.restype = ctypes.c_int
     sc.argtypes = [vp, i64, i32, i32, i64, i32, vp, vp, ctypes.c_size_t, vp]

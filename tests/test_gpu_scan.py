@@ -1,8 +1,9 @@
 """bload_segment_scan on the GPU against the oracle's recurrence, element by element.
 
-Bound used throughout (float32 arithmetic in time order against the oracle's double): at the
-k-th slot of a block (k counted from 1, an upper bound of the frame's place in its sequence)
-|gpu - oracle| <= (2k + 2) * 2^-24 * S, S = the same recurrence on |x| with |decay|.
+Bound used throughout (float32 arithmetic in time order, states handed across chunks of time as
+decay^chunk * state + the chunk's own part, against the oracle's double): at the k-th slot of a
+block (k counted from 1, an upper bound of the frame's place in its sequence)
+|gpu - oracle| <= (3k + 4) * 2^-24 * S, S = the same recurrence on |x| with |decay|.
 """
 import numpy as np
 import pytest
@@ -20,7 +21,7 @@ EPS = 2.0 ** -24
 def assert_scan_close(got, ref, scale, what):
     B, T, D = ref.shape
     k = np.arange(1, T + 1, dtype=np.float64)[None, :, None]
-    bound = (2 * k + 2) * EPS * scale.astype(np.float64)
+    bound = (3 * k + 4) * EPS * scale.astype(np.float64)
     err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
     bad = err > bound
     if bad.any():
