@@ -47,7 +47,23 @@ __global__ __launch_bounds__(kThreads) void counts_kernel(const int32_t* __restr
     deleted = wave_sum(deleted);
 #pragma unroll
     for (int d = kWave / 2; d > 0; d >>= 1) longest = max(longest, __shfl_down(longest, d, kWave));
+    // one set of atomics per workgroup
+    __shared__ unsigned long long s_part[kThreads / kWave][3];
+    __shared__ int32_t s_longest[kThreads / kWave];
     if (lane_id() == 0) {
+        s_part[wave_id()][0] = total;
+        s_part[wave_id()][1] = samples;
+        s_part[wave_id()][2] = deleted;
+        s_longest[wave_id()] = longest;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kThreads / kWave; ++w) {
+            total += s_part[w][0];
+            samples += s_part[w][1];
+            deleted += s_part[w][2];
+            longest = max(longest, s_longest[w]);
+        }
         if (total) atomicAdd(&acc->total, total);
         if (samples) atomicAdd(&acc->samples, samples);
         if (deleted) atomicAdd(&acc->deleted, deleted);
@@ -74,7 +90,7 @@ extern "C" bload_status bload_strategy_counts(const int32_t* d_lengths, int64_t 
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     CountAcc* acc = static_cast<CountAcc*>(d_workspace);
-    const uint32_t grid = (uint32_t)(ceil_div(n_seq, kThreads) < 2048 ? ceil_div(n_seq, kThreads) : 2048);
+    const uint32_t grid = (uint32_t)(ceil_div(n_seq, kThreads) < 512 ? ceil_div(n_seq, kThreads) : 512);
     hipLaunchKernelGGL(counts_clear_kernel, dim3(1), dim3(1), 0, stream, acc);
     hipLaunchKernelGGL(counts_kernel, dim3(grid), dim3(kThreads), 0, stream, d_lengths, n_seq, t_chunk,
                        acc);

@@ -53,11 +53,16 @@ def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", type=int, required=True)
     ap.add_argument("--trace", required=True)
-    ap.add_argument("--fetch", required=True)
-    ap.add_argument("--write", required=True)
+    ap.add_argument("--fetch", help="omit both counter files to summarise the kernel trace only")
+    ap.add_argument("--write")
+    ap.add_argument("--flags", default="", help="further bench.py flags the runs were made with, "
+                                                "e.g. '--plan random-fit --scan'")
+    ap.add_argument("--tag", default="", help="suffix of the summary's file name for such a run")
     ap.add_argument("--bench", required=True, help="the JSON line bench.py printed in the trace run")
     args = ap.parse_args()
     w = args.workload
+    flags = (" " + args.flags.strip()) if args.flags.strip() else ""
+    tag = ("_" + args.tag) if args.tag else ""
     with open(args.bench) as f:
         bench = json.loads([ln for ln in f if ln.startswith("{")][-1])
     cfg = bench["config"]["workload"]
@@ -66,7 +71,7 @@ def main() -> None:
     lines = [f"# rocprofv3 kernel trace of bench.py, workload {cfg}", "",
              "Command (MI355X box, repository root):", "",
              "    rocprofv3 --kernel-trace --stats --output-format csv -d gpurun_out/prof/kt -o kt -- \\",
-             f"        python3 bench.py --workload {w} --steps 10 --warmup 2 --no-cpu-baseline --calibrate-copy",
+             f"        python3 bench.py --workload {w} --steps 10 --warmup 2 --no-cpu-baseline --calibrate-copy{flags}",
              "", "Summarised by `python -m paper_2310_10879_amd.profile_summary` from kt_kernel_stats.csv.", "",
              "| kernel | calls | avg ns | min ns | max ns | % of GPU time |", "|---|---|---|---|---|---|"]
     with open(args.trace) as f:
@@ -75,11 +80,19 @@ def main() -> None:
                          f"{r['MaxNs']} | {float(r['Percentage']):.2f} |")
     ph = bench["phases_ms"]
     lines += ["", f"bench.py's event timing in the same run (ms per call): plan {ph['plan']:.4f}, "
-              f"pack {ph['pack']:.4f}, segment_reduce {ph['segment_reduce']:.4f}; "
+              f"pack {ph['pack']:.4f}, segment_reduce {ph['segment_reduce']:.4f}"
+              + (f", segment_scan {ph['segment_scan']:.4f}" if "segment_scan" in ph else "") + "; "
               f"pack roofline: {bench['roofline']['achieved']:.0f} GB/s of algorithmic bytes = "
               f"{100 * bench['roofline']['frac']:.1f} % of {bench['roofline']['peak']:.0f} GB/s."]
-    with open(os.path.join(ROOT, "profiles", f"bload_workload{w}_kernel_trace.md"), "w") as f:
+    if "segment_scan" in bench:
+        lines += [f"segment_scan: {bench['segment_scan']['algorithmic_GBps']:.0f} GB/s of algorithmic bytes "
+                  f"({bench['segment_scan']['algorithmic_bytes_per_launch'] / 1e9:.3f} GB per call: valid payload read, "
+                  "every output element and both flag planes)."]
+    with open(os.path.join(ROOT, "profiles", f"bload_workload{w}{tag}_kernel_trace.md"), "w") as f:
         f.write("\n".join(lines) + "\n")
+    if not args.fetch or not args.write:
+        print(lines[-1])
+        return
 
     # ---- HBM counters
     fetch, write = counter_means(args.fetch), counter_means(args.write)
