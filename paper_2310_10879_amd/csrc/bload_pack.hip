@@ -124,8 +124,11 @@ __device__ __forceinline__ int run_of_slot(const RunTable<MAXRUNS>& tab, int n, 
 // block's positions followed by a walk over consecutive positions), so it
 // runs on the scalar unit with a handful of dependent scalar loads.
 
-constexpr int kWideMinFrame = 512;                  // smallest frame the wide kernel takes
+constexpr int kWideMinFrame = 64;                   // smallest frame the wide kernel takes
 constexpr int kWideTile = 4096;                     // tile used: one 16-byte vector per thread
+constexpr int kWideWalkRuns = 2;                    // up to this many runs in a tile are walked one by one
+constexpr int kWideRuns = 128;                      // shuffled positions looked up per tile; a power of two
+static_assert(kWideTile / kWideMinFrame + 2 <= kWideRuns, "a tile's runs must fit the look-up window");
 
 typedef vec16 __attribute__((aligned(1))) vec16_unaligned;
 
@@ -187,14 +190,14 @@ __device__ __forceinline__ void write_range(uint8_t* packed, int64_t lo, int64_t
     }
 }
 
-// Start-table entries of global slots [lo, hi) (fewer than 64): lane k of the
-// calling wave writes slot lo + k.  frame0 = frame index of slot lo, or -1 for padding.
+// Start-table entries of global slots [lo, hi): lane k of the calling wave writes the slots
+// lo + k, lo + k + 64, ...  frame0 = frame index of slot lo, or -1 for padding.
 __device__ __forceinline__ void write_slots(const PackArgs& a, int64_t lo, int64_t hi, int32_t seq,
                                             int64_t frame0)
 {
-    const int64_t g = lo + lane_id();
-    if (g < hi) {
-        const int32_t fid = frame0 < 0 ? -1 : (int32_t)(frame0 + lane_id());
+    for (int64_t k = lane_id(); lo + k < hi; k += kWave) {
+        const int64_t g = lo + k;
+        const int32_t fid = frame0 < 0 ? -1 : (int32_t)(frame0 + k);
         a.seq_id[g] = frame0 < 0 ? -1 : seq;
         a.frame_idx[g] = fid;
         a.reset[g] = (uint8_t)(fid == 0);
@@ -261,8 +264,8 @@ __global__ __launch_bounds__(kThreads) void pack_wide_kernel(
                 store_stream(reinterpret_cast<vec16*>(a.packed + D0) + threadIdx.x, x);
                 if (table_wave) {
                     // frames t of this run with D0 <= run_lo + t * F < D1
-                    const int64_t t = floor_div(D0 - run_lo + F - 1, F, inv_frame_bytes) + lane_id();
-                    if (run_lo + t * F < D1 && t < len) {
+                    for (int64_t t = floor_div(D0 - run_lo + F - 1, F, inv_frame_bytes) + lane_id();
+                         run_lo + t * F < D1 && t < len; t += kWave) {
                         a.seq_id[g + t] = (int32_t)i;
                         a.frame_idx[g + t] = (int32_t)t;
                         a.reset[g + t] = (uint8_t)(t == 0);
@@ -276,8 +279,8 @@ __global__ __launch_bounds__(kThreads) void pack_wide_kernel(
                 const vec16 z = {0u, 0u, 0u, 0u};
                 store_stream(reinterpret_cast<vec16*>(a.packed + D0) + threadIdx.x, z);
                 if (table_wave) {
-                    const int64_t slot = floor_div(D0 + F - 1, F, inv_frame_bytes) + lane_id();
-                    if (slot * F < D1) {
+                    for (int64_t slot = floor_div(D0 + F - 1, F, inv_frame_bytes) + lane_id(); slot * F < D1;
+                         slot += kWave) {
                         a.seq_id[slot] = -1;
                         a.frame_idx[slot] = -1;
                         a.reset[slot] = 0;
@@ -295,32 +298,121 @@ __global__ __launch_bounds__(kThreads) void pack_wide_kernel(
     const int64_t m_lo = gs_lo + ((gs_lo * F < D0) ? 1 : 0);
     const int64_t m_hi = min(gs_hi, a.total_slots);
 
-    // runs in destination order from there on, zeros in the gaps (block tails)
-    int64_t cursor = D0;          // payload bytes written so far
-    int64_t mcursor = m_lo;       // start-table slots written so far
-    for (; p < n_seq; ++p) {
-        const uint32_t i = (uint32_t)order[p];
-        if (i >= (uint32_t)n_seq) break;
-        const int64_t g = (int64_t)block_of_seq[i] * T + offset_of_seq[i];
-        if (g >= gs_hi) break;
-        const int64_t len = lengths[i];
-        if (g + len <= gs_lo) continue;           // ends before the tile: the tile starts in padding
-        const int64_t run_lo = g * F;
-        const int64_t lo = max(max(run_lo, D0), cursor);
-        const int64_t hi = min(run_lo + len * F, D1);
-        if (hi > lo) {
-            if (lo > cursor) write_range<true>(a.packed, cursor, lo, nullptr);
-            write_range<false>(a.packed, lo, hi, a.src + src_offsets[i] * F + (lo - run_lo));
-            cursor = hi;
+    // A tile that few runs touch walks them one after the other (their look-ups are scalar
+    // loads, the whole workgroup copies each run's part).  The shuffled position in front of
+    // the next tile bounds the number of runs from above.
+    const int32_t p_next = (tile + 1 < gridDim.x) ? min(max(first_pos[tile + 1], 0), n_seq) : n_seq - 1;
+    if (p_next - p + 1 <= kWideWalkRuns) {
+        // runs in destination order from there on, zeros in the gaps (block tails)
+        int64_t cursor = D0;          // payload bytes written so far
+        int64_t mcursor = m_lo;       // start-table slots written so far
+        for (; p < n_seq; ++p) {
+            const uint32_t i = (uint32_t)order[p];
+            if (i >= (uint32_t)n_seq) break;
+            const int64_t g = (int64_t)block_of_seq[i] * T + offset_of_seq[i];
+            if (g >= gs_hi) break;
+            const int64_t len = lengths[i];
+            if (g + len <= gs_lo) continue;           // ends before the tile: the tile starts in padding
+            const int64_t run_lo = g * F;
+            const int64_t lo = max(max(run_lo, D0), cursor);
+            const int64_t hi = min(run_lo + len * F, D1);
+            if (hi > lo) {
+                if (lo > cursor) write_range<true>(a.packed, cursor, lo, nullptr);
+                write_range<false>(a.packed, lo, hi, a.src + src_offsets[i] * F + (lo - run_lo));
+                cursor = hi;
+            }
+            if (table_wave) {
+                const int64_t s_lo = max(g, mcursor), s_hi = min(g + len, m_hi);
+                if (s_lo > mcursor) write_slots(a, mcursor, s_lo, -1, -1);
+                if (s_hi > s_lo) { write_slots(a, s_lo, s_hi, (int32_t)i, s_lo - g); mcursor = s_hi; }
+            }
         }
-        if (table_wave) {
-            const int64_t s_lo = max(g, mcursor), s_hi = min(g + len, m_hi);
-            if (s_lo > mcursor) write_slots(a, mcursor, s_lo, -1, -1);
-            if (s_hi > s_lo) { write_slots(a, s_lo, s_hi, (int32_t)i, s_lo - g); mcursor = s_hi; }
+        if (cursor < D1) write_range<true>(a.packed, cursor, D1, nullptr);
+        if (table_wave && mcursor < m_hi) write_slots(a, mcursor, m_hi, -1, -1);
+        return;
+    }
+
+    // Every other tile: the runs that touch it are looked up side by side (thread k takes the
+    // k-th shuffled position from p on), so that the cost does not grow with their number, and
+    // every thread then finds the run of its own 16 bytes.  A frame of kWideMinFrame bytes or
+    // more puts at most kWideTile / kWideMinFrame + 2 runs into a tile.
+    __shared__ int64_t s_run_lo[kWideRuns + 1];     // first packed byte of the run; INT64_MAX: no run
+    __shared__ int64_t s_run_hi[kWideRuns];         // one past its last packed byte
+    __shared__ int64_t s_run_src[kWideRuns];        // source byte that goes to s_run_lo
+    __shared__ int32_t s_run_seq[kWideRuns];
+    const int tid = (int)threadIdx.x;
+    if (tid <= kWideRuns) {
+        int64_t lo = INT64_MAX, hi = 0, from = 0;
+        int32_t seq = -1;
+        const int64_t pos = (int64_t)p + tid;
+        if (tid < kWideRuns && pos < n_seq) {
+            const uint32_t i = (uint32_t)order[pos];
+            if (i < (uint32_t)n_seq) {
+                const int64_t g = (int64_t)block_of_seq[i] * T + offset_of_seq[i];
+                if (g < gs_hi) {
+                    lo = g * F;
+                    hi = lo + (int64_t)lengths[i] * F;
+                    from = src_offsets[i] * F;
+                    seq = (int32_t)i;
+                }
+            }
+        }
+        s_run_lo[tid] = lo;
+        if (tid < kWideRuns) {
+            s_run_hi[tid] = hi;
+            s_run_src[tid] = from;
+            s_run_seq[tid] = seq;
         }
     }
-    if (cursor < D1) write_range<true>(a.packed, cursor, D1, nullptr);
-    if (table_wave && mcursor < m_hi) write_slots(a, mcursor, m_hi, -1, -1);
+    __syncthreads();
+    // last gathered run that starts at or before packed byte x, -1 if none
+    // (a binary search over the first `span` entries, span = a power of two that covers them)
+    int span = 1;
+    while (span < min(p_next - p + 2, kWideRuns)) span <<= 1;
+    auto run_at = [&](int64_t x) {
+        int k = -1;
+        for (int step = span >> 1; step >= 1; step >>= 1)
+            if (s_run_lo[k + step] <= x) k += step;
+        if (s_run_lo[k + 1] <= x) ++k;
+        return k;
+    };
+
+    for (int64_t x0 = D0 + 16 * (int64_t)tid; x0 < D1; x0 += 16 * (int64_t)kThreads) {
+        int k = run_at(x0);
+        const int64_t next_lo = s_run_lo[k + 1];
+        const int64_t lo = k >= 0 ? s_run_lo[k] : 0, hi = k >= 0 ? s_run_hi[k] : 0;
+        vec16* dst = reinterpret_cast<vec16*>(a.packed + x0);
+        if (x0 + 16 <= D1 && x0 + 16 <= hi) {                           // inside one run
+            const uint8_t* from = a.src + s_run_src[k] + (x0 - lo);
+            store_stream(dst, __builtin_nontemporal_load(reinterpret_cast<const vec16_unaligned*>(from)));
+        } else if (x0 + 16 <= D1 && x0 >= hi && x0 + 16 <= next_lo) {   // inside a block's zero tail
+            const vec16 z = {0u, 0u, 0u, 0u};
+            store_stream(dst, z);
+        } else {                                                        // a border inside: byte by byte
+            for (int j = 0; j < 16 && x0 + j < D1; ++j) {
+                const int64_t x = x0 + j;
+                while (s_run_lo[k + 1] <= x) ++k;
+                uint8_t v = 0;
+                if (k >= 0 && x < s_run_hi[k]) v = a.src[s_run_src[k] + (x - s_run_lo[k])];
+                a.packed[x] = v;
+            }
+        }
+    }
+    if (table_wave) {
+        for (int64_t slot = m_lo + lane_id(); slot < m_hi; slot += kWave) {
+            const int64_t x = slot * F;
+            const int k = run_at(x);
+            int32_t seq = -1, fid = -1;
+            if (k >= 0 && x < s_run_hi[k]) {
+                seq = s_run_seq[k];
+                fid = (int32_t)(slot - floor_div(s_run_lo[k], F, inv_frame_bytes));
+            }
+            a.seq_id[slot] = seq;
+            a.frame_idx[slot] = fid;
+            a.reset[slot] = (uint8_t)(fid == 0);
+            a.valid[slot] = (uint8_t)(fid >= 0);
+        }
+    }
 }
 
 // ----------------------------------------------------------------- narrow
@@ -464,12 +556,27 @@ __global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a,
 
 using namespace bload;
 
+// Which tile shape packs faster, from what the host knows.  The 4 KiB tiles win where runs
+// (a sequence's bytes) are long: a tile inside one run is a plain copy.  The 1024-slot tiles
+// amortise their run table better where many short runs meet, and copy 16 bytes per lane when
+// frames are multiples of 16 bytes and the source is aligned.  Measured crossovers, in bytes
+// per run (bounded from above here by packed bytes / sequences).
+static bool takes_wide_tiles(int64_t frame_bytes, int64_t total_bytes, int64_t n_seq, bool src_aligned16)
+{
+    if (frame_bytes < kWideMinFrame) return false;
+    if (frame_bytes >= 512) return true;
+    const int64_t run_bytes = total_bytes / (n_seq > 0 ? n_seq : 1);
+    const bool narrow_copies_vectors = frame_bytes % 16 == 0 && src_aligned16;
+    return run_bytes >= (narrow_copies_vectors ? 24 * 1024 : 4 * 1024);
+}
+
 extern "C" size_t bload_pack_workspace_bytes(int64_t num_blocks, int32_t t_blk, int64_t frame_bytes)
 {
     if (num_blocks <= 0 || t_blk < 1 || frame_bytes < 1) return 0;
     const int64_t total_slots = num_blocks * (int64_t)t_blk;
     if (total_slots >= ((int64_t)1 << 40) || total_slots > (((int64_t)1 << 52) - 1) / frame_bytes) return 0;
-    // one int32 per tile: 4 KiB of packed tensor (wide frames) or 1024 slots (narrow frames)
+    // one int32 per tile: 4 KiB of packed tensor or 1024 slots; frames that may take either
+    // shape (the choice depends on the lengths) get room for the 4 KiB tiles, which are more
     const int64_t tiles = frame_bytes >= kWideMinFrame ? ceil_div(total_slots * frame_bytes, kWideTile)
                                                        : ceil_div(total_slots, kNarrowSlots);
     return round_up((size_t)tiles * sizeof(int32_t), 16);
@@ -523,9 +630,9 @@ extern "C" bload_status bload_pack(const void* d_src, const int64_t* d_src_offse
 
     // pass 1 (both tile shapes): where each tile starts in the shuffled order.  The
     // narrow tiles are 1024 slots, which the kernel takes as "1024 bytes of 1-byte frames".
-    const bool wide = frame_bytes >= kWideMinFrame;
     const int64_t total_bytes = total_slots * frame_bytes;
     if (total_bytes >= ((int64_t)1 << 52)) return BLOAD_EOVERFLOW;
+    const bool wide = takes_wide_tiles(frame_bytes, total_bytes, n_seq, aligned_to(d_src, 16));
     const int64_t tiles = wide ? ceil_div(total_bytes, kWideTile) : ceil_div(total_slots, kNarrowSlots);
     if (tiles > INT32_MAX) return BLOAD_EOVERFLOW;
     if (!d_workspace) return BLOAD_EINVAL;

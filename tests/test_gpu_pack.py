@@ -45,6 +45,25 @@ def test_pack_with_device_plan(F):
         run_case(n, T, F, kind, seed=0, plan_from="gpu")
 
 
+@pytest.mark.parametrize("F", [64, 65, 100, 256, 320, 333, 500, 511])
+def test_pack_middle_frames_take_either_tile_shape(F):
+    """Frames of 64..511 bytes go through the 4 KiB tiles when sequences are long and through the
+    1024-slot tiles when they are short: both, and the mixes in between, against the oracle."""
+    for n, T, lo, hi in [(40, 2000, 1000, 2000),      # every run far longer than a tile
+                         (3000, 64, 1, 3),            # dozens of runs in every 4 KiB
+                         (600, 300, 40, 120),         # a few tiles per run
+                         (400, 700, 1, 700)]:         # everything at once
+        rng = np.random.default_rng(F * 13 + n)
+        L = rng.integers(lo, hi + 1, size=n).astype(np.int32)
+        so = workloads.src_offsets(L)
+        src = workloads.tagged_source(L, F)
+        ref_plan = oracle.plan(L, T, oracle.order(n, 5))
+        ref = oracle.pack(src, so, L, ref_plan, F)
+        print(f"pack F={F} n={n} T={T} L in [{lo}, {hi}]", flush=True)
+        out = gpu_pack_guarded(src, so, L, upload_plan(ref_plan, n), F)
+        assert_packed_equal(out, ref, f"F={F} n={n} T={T}: ")
+
+
 def test_pack_degenerate_blocks():
     # every block full, every block one frame, blocks of unit sequences
     for n, T, L in [(50, 8, np.full(50, 8)), (50, 8, np.ones(50)), (50, 8, np.full(50, 5)),
