@@ -229,7 +229,8 @@ def main() -> int:
         },
         "strategy_counts": strategies,
         "roofline": {
-            "kernel": "pack_wide_kernel" if F >= 512 else "pack_narrow_kernel",
+            "kernel": "pack_wide_kernel" if bload.bload_pack_tile_bytes(N, B, T, F, d_src.data_ptr() % 16 == 0)
+            else "pack_narrow_kernel",
             "bound": "hbm",
             "achieved": pack_gbps,
             "peak": HBM_PEAK_GBPS,

@@ -199,6 +199,13 @@ bload_status bload_plan_shard(const int32_t* d_order, const int32_t* d_block_of_
  * Every byte of the five outputs is written exactly once (no prior memset is
  * needed).  Asynchronous on `hip_stream`.  n_seq = 0 / num_blocks = 0: no-op.
  */
+/* Which of its two kernels bload_pack launches for these sizes: 4096 when the packed
+ * tensor is cut into tiles of 4096 bytes (pack_wide_kernel), 0 when it is cut into
+ * tiles of 1024 slots (pack_narrow_kernel), also for sizes bload_pack refuses.
+ * src_aligned_16: whether d_src is 16-byte aligned.  For profiling and reports. */
+int32_t bload_pack_tile_bytes(int64_t n_seq, int64_t num_blocks, int32_t t_blk, int64_t frame_bytes,
+                              int32_t src_aligned_16);
+
 size_t bload_pack_workspace_bytes(int64_t num_blocks, int32_t t_blk, int64_t frame_bytes);
 
 bload_status bload_pack(const void* d_src, const int64_t* d_src_offsets, const int32_t* d_lengths,

@@ -51,6 +51,8 @@ _lib.bload_plan_shard.argtypes = [_vp, _vp, _vp, _i64, _i64, _i32, _i32, _vp, _v
                                   ctypes.POINTER(_i64), ctypes.POINTER(_i64), _vp, _sz, _vp]
 _lib.bload_pack_workspace_bytes.restype = _sz
 _lib.bload_pack_workspace_bytes.argtypes = [_i64, _i32, _i64]
+_lib.bload_pack_tile_bytes.restype = _i32
+_lib.bload_pack_tile_bytes.argtypes = [_i64, _i64, _i32, _i64, _i32]
 _lib.bload_pack.restype = ctypes.c_int
 _lib.bload_pack.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i32, _i64,
                             _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -328,3 +330,10 @@ def bload_segment_scan(packed: torch.Tensor, reset: torch.Tensor, valid: torch.T
                                  workspace.numel() * workspace.element_size(), _stream())
     _check(st)
     return out
+
+
+def bload_pack_tile_bytes(n_seq: int, num_blocks: int, t_blk: int, frame_bytes: int,
+                          src_aligned_16: bool = True) -> int:
+    """4096 if ``bload_pack`` cuts the packed tensor into 4 KiB tiles for these sizes
+    (pack_wide_kernel), 0 if into tiles of 1024 slots (pack_narrow_kernel)."""
+    return int(_lib.bload_pack_tile_bytes(n_seq, num_blocks, t_blk, frame_bytes, int(src_aligned_16)))

@@ -570,6 +570,15 @@ static bool takes_wide_tiles(int64_t frame_bytes, int64_t total_bytes, int64_t n
     return run_bytes >= (narrow_copies_vectors ? 24 * 1024 : 4 * 1024);
 }
 
+extern "C" int32_t bload_pack_tile_bytes(int64_t n_seq, int64_t num_blocks, int32_t t_blk,
+                                         int64_t frame_bytes, int32_t src_aligned_16)
+{
+    if (n_seq < 0 || num_blocks <= 0 || t_blk < 1 || frame_bytes < 1) return 0;
+    const int64_t total_slots = num_blocks * (int64_t)t_blk;
+    if (total_slots >= ((int64_t)1 << 40) || total_slots > (((int64_t)1 << 52) - 1) / frame_bytes) return 0;
+    return takes_wide_tiles(frame_bytes, total_slots * frame_bytes, n_seq, src_aligned_16 != 0) ? kWideTile : 0;
+}
+
 extern "C" size_t bload_pack_workspace_bytes(int64_t num_blocks, int32_t t_blk, int64_t frame_bytes)
 {
     if (num_blocks <= 0 || t_blk < 1 || frame_bytes < 1) return 0;

@@ -118,6 +118,13 @@ def test_argument_checks_need_no_gpu(lib):
     need = 4 * -(-180 * 600 * 37632 // 4096)         # one int32 per 4 KiB tile
     assert need <= f(180, 600, 37632) < need + 16 and f(180, 600, 37632) % 16 == 0
     assert f(180, 600, 4) == 4 * -(-180 * 600 // 1024) + 8 and f(0, 600, 4096) == 0
+    tb = lib.bload_pack_tile_bytes
+    tb.restype = i32
+    tb.argtypes = [i64, i64, i32, i64, i32]
+    assert tb(1000, 180, 600, 37632, 1) == 4096 and tb(10**6, 324084, 4096, 4, 1) == 0
+    assert tb(50000, 34576, 3000, 320, 1) == 4096          # long runs of middle-sized frames
+    assert tb(4000000, 100000, 64, 320, 1) == 0            # short runs of the same frames
+    assert tb(10, 0, 600, 64, 1) == 0 and tb(10, 5, 600, 0, 1) == 0
     lib.bload_plan_shard.restype = ctypes.c_int
     lib.bload_plan_shard.argtypes = [vp, vp, vp, i64, i64, i32, i32, vp, vp, vp,
                                      ctypes.POINTER(i64), ctypes.POINTER(i64), vp, ctypes.c_size_t, vp]
