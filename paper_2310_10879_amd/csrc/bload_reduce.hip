@@ -737,8 +737,10 @@ static ReducePlan reduce_plan(int64_t num_blocks, int32_t t_blk, int64_t feat_di
     if (p.wide) {
         p.vec = vectors ? 16 / es : 1;
         p.n_vec = (int)ceil_div(feat_dim, p.vec);
+        // a row is at most one wave wide: the last lane-slice of a frame then idles at most 63
+        // lanes, and the four waves of a workgroup walk four different chunks
         p.row_lanes_log2 = 0;
-        while ((1 << p.row_lanes_log2) < p.n_vec && p.row_lanes_log2 < 8) ++p.row_lanes_log2;
+        while ((1 << p.row_lanes_log2) < p.n_vec && p.row_lanes_log2 < 6) ++p.row_lanes_log2;
         const int rows = kThreads >> p.row_lanes_log2;
         const int64_t feat_tiles = ceil_div(p.n_vec, 1 << p.row_lanes_log2);
         // enough chunks per block for ~2048 workgroups, each at least 64 slots long
