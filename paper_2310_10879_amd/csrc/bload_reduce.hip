@@ -118,15 +118,16 @@ constexpr int kWideFlagBytes = 32768;      // LDS budget for the staged flags
 // First slot s in [t, len) whose staged flags say "valid" (WANT_VALID) or "not a
 // plain continuation: padding or a start flag" (!WANT_VALID); len if none.  The
 // lanes of a row (or of the wave, for rows wider than a wave) test one slot
-// each per step and vote; every lane of the row gets the same answer.
-template <bool WANT_VALID>
+// each per step and vote; every lane of the row gets the same answer.  WAVE_ROW:
+// the row is the whole wave, and everything here but the tested slot is wave-uniform.
+template <bool WANT_VALID, bool WAVE_ROW>
 __device__ __forceinline__ int32_t next_slot(const uint8_t* flags, int32_t t, int32_t len,
                                              int row_lanes_log2)
 {
-    const int width = row_lanes_log2 >= 6 ? kWave : (1 << row_lanes_log2);
+    const int width = WAVE_ROW ? kWave : (1 << row_lanes_log2);
     const int lane = lane_id();
-    const int base = lane & ~(width - 1);
-    const uint64_t row_mask = (width == kWave ? ~0ull : ((1ull << width) - 1ull)) << base;
+    const int base = WAVE_ROW ? 0 : lane & ~(width - 1);
+    const uint64_t row_mask = WAVE_ROW ? ~0ull : ((1ull << width) - 1ull) << base;
     for (; t < len; t += width) {
         const int32_t s = t + (lane - base);
         bool hit = false;
@@ -139,6 +140,11 @@ __device__ __forceinline__ int32_t next_slot(const uint8_t* flags, int32_t t, in
     }
     return len;
 }
+
+// Elements of LDS scratch per lane for the transposed stores: the lane's VEC values plus
+// padding against bank conflicts (a multiple of 4 for floats, which move 16 bytes at a time).
+template <typename Acc, int VEC>
+__host__ __device__ constexpr int kScratchStride() { return sizeof(Acc) == 4 ? VEC + 4 : VEC + 1; }
 
 // Store the VEC accumulators of every lane of a row to dst[feat0 ...].  A lane
 // holds VEC consecutive features, so storing straight from the registers
@@ -158,20 +164,47 @@ __device__ __forceinline__ void store_row(Acc* dst_row, int64_t feat0, const Acc
         return;
     }
     const int lane = lane_id();
+    constexpr int S = kScratchStride<Acc, VEC>();
     // element e of the wave's 64 * VEC span lives in lane e / VEC, register e % VEC
+    if constexpr (sizeof(Acc) == 4 && VEC % 4 == 0) {
+      if ((reinterpret_cast<uintptr_t>(dst_row) & 15) == 0) {
+        // four floats at a time: VEC / 4 stores of 1 KiB per wave
+        typedef float float4v __attribute__((ext_vector_type(4)));
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) scratch[lane * (VEC + 1) + k] = v[k];
+        for (int k = 0; k < VEC; k += 4) {
+            const float4v q = {(float)v[k], (float)v[k + 1], (float)v[k + 2], (float)v[k + 3]};
+            *reinterpret_cast<float4v*>(reinterpret_cast<float*>(scratch) + lane * S + k) = q;
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int j = 0; j < VEC / 4; ++j) {
+            const int e = j * kWave * 4 + lane * 4;
+            const float4v q = *reinterpret_cast<const float4v*>(reinterpret_cast<const float*>(scratch) +
+                                                                (e / VEC) * S + (e % VEC));
+            if (wave_feat0 + e < feat_dim)
+                *reinterpret_cast<float4v*>(reinterpret_cast<float*>(dst_row) + wave_feat0 + e) = q;
+        }
+        __builtin_amdgcn_wave_barrier();
+        return;
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) scratch[lane * S + k] = v[k];
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int j = 0; j < VEC; ++j) {
         const int e = j * kWave + lane;
-        const Acc x = scratch[(e / VEC) * (VEC + 1) + (e % VEC)];
+        const Acc x = scratch[(e / VEC) * S + (e % VEC)];
         if (wave_feat0 + e < feat_dim) dst_row[wave_feat0 + e] = x;
     }
     __builtin_amdgcn_wave_barrier();
 }
 
-template <typename ElemT, int VEC>
+// WAVE_ROW: a row of lanes is exactly one wave.  Its chunk, the pieces found in it and the
+// addresses of the frames are then the same for all lanes of the wave, and saying so (the row
+// index goes through readfirstlane) lets the compiler keep them in scalar registers and address
+// the loads as scalar base + lane offset.
+template <typename ElemT, int VEC, bool WAVE_ROW>
 __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
 {
     typedef typename Elem<ElemT>::Acc Acc;
@@ -203,8 +236,8 @@ __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
     }
     __syncthreads();
 
-    const int row = tid >> a.row_lanes_log2;
-    const int col = tid & ((1 << a.row_lanes_log2) - 1);
+    const int row = WAVE_ROW ? __builtin_amdgcn_readfirstlane(tid >> 6) : tid >> a.row_lanes_log2;
+    const int col = WAVE_ROW ? lane_id() : tid & ((1 << a.row_lanes_log2) - 1);
     const int64_t q = q_base + row;
     if (q >= a.total_chunks) return;
     // which lane-slice of the frame; the surplus lanes of a row stay alive (they
@@ -219,7 +252,8 @@ __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
     const int64_t g = b * T + t0;
     const uint8_t* flags = s_flags + row * stride + 1;      // flags[-1] = the slot before the chunk
     const int64_t frame_bytes = (int64_t)a.feat_dim * (int64_t)sizeof(ElemT);
-    const uint8_t* lane_src = a.packed + g * frame_bytes + (int64_t)fv * VEC * (int64_t)sizeof(ElemT);
+    const uint8_t* chunk_src = a.packed + g * frame_bytes;                 // the chunk's first frame
+    const uint32_t lane_off = (uint32_t)fv * VEC * (uint32_t)sizeof(ElemT);  // the lane's place in a frame
     const int64_t feat0 = (int64_t)fv * VEC;
     const bool writes_desc = (col == 0 && feat_tile == 0 && a.desc != nullptr);
     typedef typename OutOf<Acc>::T Out;
@@ -231,9 +265,9 @@ __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
     // wave lies inside one row
     Acc* scratch = nullptr;
     const int64_t wave_feat0 = (int64_t)(fv_raw - lane_id()) * VEC;   // first feature of the wave
-    if (VEC > 1 && a.row_lanes_log2 >= 6) {
+    if (VEC > 1 && WAVE_ROW) {
         const size_t flag_bytes = ((size_t)rows * stride + 15) & ~(size_t)15;
-        scratch = reinterpret_cast<Acc*>(s_flags + flag_bytes) + (size_t)wave_id() * kWave * (VEC + 1);
+        scratch = reinterpret_cast<Acc*>(s_flags + flag_bytes) + (size_t)wave_id() * kWave * kScratchStride<Acc, VEC>();
     }
 
     Acc acc[VEC];
@@ -244,21 +278,21 @@ __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
     // staged flags, sum it with unconditional loads, hand the sum on.
     int32_t t = 0;
     for (;;) {
-        t = next_slot<true>(flags, t, len, a.row_lanes_log2);           // next valid slot
+        t = next_slot<true, WAVE_ROW>(flags, t, len, a.row_lanes_log2);    // next valid slot
         if (t >= len) break;
         // a segment starts at a start flag, at the block's first slot, or behind padding;
         // a valid first slot of the chunk that does none of these continues the segment
         // of the chunk before
         const bool head_open = t == 0 && !(flags[0] & 2) && (flags[-1] & 1);
-        const int32_t e = next_slot<false>(flags, t + 1, len, a.row_lanes_log2);  // padding or a start
+        const int32_t e = next_slot<false, WAVE_ROW>(flags, t + 1, len, a.row_lanes_log2);  // padding or a start
 #pragma unroll
         for (int k = 0; k < VEC; ++k) acc[k] = 0;
-        const uint8_t* p = lane_src + (int64_t)t * frame_bytes;
+        const uint8_t* p = chunk_src + (int64_t)t * frame_bytes;          // frame of slot s, lane 0
         int32_t s = t;
         for (; s + kWideUnroll <= e; s += kWideUnroll) {
             LaneData<ElemT, VEC> x[kWideUnroll];
 #pragma unroll
-            for (int u = 0; u < kWideUnroll; ++u) x[u].load(p + (int64_t)u * frame_bytes);
+            for (int u = 0; u < kWideUnroll; ++u) x[u].load(p + (int64_t)u * frame_bytes + lane_off);
 #pragma unroll
             for (int u = 0; u < kWideUnroll; ++u) {
 #pragma unroll
@@ -273,7 +307,7 @@ __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
             LaneData<ElemT, VEC> x[kWideUnroll];
 #pragma unroll
             for (int u = 0; u < kWideUnroll; ++u)
-                x[u].load(p + (int64_t)min(u, left - 1) * frame_bytes);
+                x[u].load(p + (int64_t)min(u, left - 1) * frame_bytes + lane_off);
 #pragma unroll
             for (int u = 0; u < kWideUnroll; ++u) {
                 if (u < left) {
@@ -779,13 +813,19 @@ static void launch_wide(const ReducePlan& p, const ReduceArgs& a, hipStream_t st
     const dim3 grid((uint32_t)(ceil_div(p.total_chunks, rows) * a.feat_tiles));
     size_t lds = (size_t)rows * (size_t)(p.chunk + 2);
     if (p.vec > 1 && p.row_lanes_log2 >= 6)     // + the per-wave scratch of the transposed stores
-        lds = round_up(lds, 16) + (size_t)(kThreads / kWave) * kWave * (p.vec + 1) *
+        lds = round_up(lds, 16) + (size_t)(kThreads / kWave) * kWave *
+                                      kScratchStride<typename Elem<ElemT>::Acc, 16 / (int)sizeof(ElemT)>() *
                                       sizeof(typename Elem<ElemT>::Acc);
-    if (p.vec > 1)
-        hipLaunchKernelGGL((reduce_wide_kernel<ElemT, 16 / (int)sizeof(ElemT)>), grid, dim3(kThreads),
-                           lds, stream, a);
+    constexpr int kVec = 16 / (int)sizeof(ElemT);
+    const bool wave_row = p.row_lanes_log2 == 6;
+    if (p.vec > 1 && wave_row)
+        hipLaunchKernelGGL((reduce_wide_kernel<ElemT, kVec, true>), grid, dim3(kThreads), lds, stream, a);
+    else if (p.vec > 1)
+        hipLaunchKernelGGL((reduce_wide_kernel<ElemT, kVec, false>), grid, dim3(kThreads), lds, stream, a);
+    else if (wave_row)
+        hipLaunchKernelGGL((reduce_wide_kernel<ElemT, 1, true>), grid, dim3(kThreads), lds, stream, a);
     else
-        hipLaunchKernelGGL((reduce_wide_kernel<ElemT, 1>), grid, dim3(kThreads), lds, stream, a);
+        hipLaunchKernelGGL((reduce_wide_kernel<ElemT, 1, false>), grid, dim3(kThreads), lds, stream, a);
 }
 
 template <typename ElemT>
