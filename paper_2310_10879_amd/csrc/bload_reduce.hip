@@ -4,7 +4,8 @@
 // to frame drop it where a new sequence begins).
 //
 // A segment is a maximal run of valid slots inside one block that begins at a
-// reset flag (or at the block's first slot) and contains no other reset flag.
+// start flag, at the block's first slot or behind a padding slot, and contains
+// no other start flag.
 // Time is cut into chunks; every chunk reduces the pieces of segments that lie
 // in it.  A piece that is a whole segment goes straight to the output.  A
 // piece cut by a chunk border goes to a partial buffer: "head" partial = the
@@ -15,8 +16,9 @@
 //
 // Two layouts of the work:
 //   wide   (a frame is >= 64 bytes): lanes across the features of a frame, each
-//          row of lanes walks one chunk of time serially with several loads in
-//          flight, restarting its accumulators at every start flag.
+//          row of lanes (at most one wave) walks one chunk of time serially
+//          with several loads in flight, restarting its accumulators at every
+//          start flag.
 //   narrow (small frames, e.g. one token): lanes across time, 8 consecutive
 //          slots per lane, segmented scan over the workgroup with the segment
 //          breaks as heads and a carry between lanes and waves.
@@ -117,7 +119,7 @@ constexpr int kWideFlagBytes = 32768;      // LDS budget for the staged flags
 
 // First slot s in [t, len) whose staged flags say "valid" (WANT_VALID) or "not a
 // plain continuation: padding or a start flag" (!WANT_VALID); len if none.  The
-// lanes of a row (or of the wave, for rows wider than a wave) test one slot
+// lanes of a row (a whole wave, or an aligned part of one) test one slot
 // each per step and vote; every lane of the row gets the same answer.  WAVE_ROW:
 // the row is the whole wave, and everything here but the tested slot is wave-uniform.
 template <bool WANT_VALID, bool WAVE_ROW>
