@@ -779,8 +779,11 @@ static ReducePlan reduce_plan(int64_t num_blocks, int32_t t_blk, int64_t feat_di
         while ((1 << p.row_lanes_log2) < p.n_vec && p.row_lanes_log2 < 6) ++p.row_lanes_log2;
         const int rows = kThreads >> p.row_lanes_log2;
         const int64_t feat_tiles = ceil_div(p.n_vec, 1 << p.row_lanes_log2);
-        // enough chunks per block for ~2048 workgroups, each at least 64 slots long
-        int64_t want = ceil_div((int64_t)2048 * rows, num_blocks * feat_tiles);
+        // Enough chunks per block for ~1024 workgroups (four per compute unit, as many as are
+        // resident at once), each at least 64 slots long.  No more: reads at full rate need few
+        // waves in flight, while every chunk border costs partial sums, and writes mixed into the
+        // read stream cost far more than their bytes.
+        int64_t want = ceil_div((int64_t)1024 * rows, num_blocks * feat_tiles);
         const int64_t most = t_blk / 64 > 0 ? t_blk / 64 : 1;
         if (want > most) want = most;
         if (want < 1) want = 1;

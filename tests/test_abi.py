@@ -65,7 +65,8 @@ def test_workspace_queries(lib):
     assert f(324084, 4096, 1, 3) == tiles * (16 + 8 + 8)   # a descriptor and two int64 partials each
     assert f(5, 2048, 1, 3) == 0                   # tiles that are whole blocks cut nothing
     assert f(34576, 3000, 80, 2) == 0              # one chunk per block
-    assert f(180, 600, 37632, 0) > 0               # video blocks are cut in time
+    assert f(180, 600, 37632, 0) == 0              # enough blocks x lane-slices: one chunk per block
+    assert f(79, 3000, 2048, 1) > 0                # few blocks: cut in time, partial sums needed
     assert f(0, 600, 8, 0) == 0 and f(5, 0, 8, 0) == 0 and f(5, 8, 8, 7) == 0
 
 
