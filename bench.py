@@ -72,7 +72,7 @@ def main() -> int:
                          "rocprofv3 HBM counters are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: the packer runs on a single MI355X and this build has "
+        print("bench.py measures one GPU: the packer runs on a single MI355X and the library has "
               "no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         return 2
 

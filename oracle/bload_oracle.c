@@ -35,7 +35,7 @@
  * forms and a brute-force optimum on tiny inputs; frame-exactly-once decoding
  * of a tagged payload; reductions of payloads with closed-form sums; the
  * paper's printed pad-to-longest count.  The identity of the permutation (which
- * bijection a seed gives) is a free choice of this build: "parity unpinned"
+ * bijection a seed gives) is a free choice of this implementation: "parity unpinned"
  * beyond those properties.
  */
 #include <stdint.h>
@@ -212,7 +212,7 @@ double bload_oracle_half_to_double(uint16_t h)
 /* dtype: 0 = u8, 1 = f16, 2 = f32, 3 = i32.   op: 0 = sum, 1 = mean.
  * out is float[n, feat_dim] for dtypes 0..2 (accumulated in double, rounded
  * once), int64[n, feat_dim] for i32 (exact; mean = sum / L truncated toward
- * zero is not defined by the build and is refused by returning 1). */
+ * zero is not defined here and is refused by returning 1). */
 int bload_oracle_segment_reduce(const void* src, const int64_t* src_offsets,
                                 const int32_t* lengths, int64_t n, int64_t feat_dim,
                                 int dtype, int op, void* out)

@@ -1,20 +1,20 @@
 """Condense rocprofv3 CSV output of `bench.py` runs into the short summaries kept under profiles/.
 
     python -m paper_2310_10879_amd.profile_summary --workload 2 \
-        --trace  gpurun_out/prof/kt/kt_kernel_stats.csv \
-        --fetch  gpurun_out/prof/fetch/fetch_counter_collection.csv \
-        --write  gpurun_out/prof/write/write_counter_collection.csv \
-        --bench  gpurun_out/prof/kt.json
+        --trace  $OUT/kt/kt_kernel_stats.csv \
+        --fetch  $OUT/fetch/fetch_counter_collection.csv \
+        --write  $OUT/write/write_counter_collection.csv \
+        --bench  $OUT/kt.json
 
-The three rocprofv3 runs that produce those files (each a run of its own, from the
-repository root on the MI355X machine; `--calibrate-copy` adds a plain 1 GiB elementwise copy
+OUT is any scratch directory.  The three rocprofv3 runs that produce those files (each a run of its own, from the
+repository root on the MI355X; `--calibrate-copy` adds a plain 1 GiB elementwise copy
 whose known size scales the two HBM counters):
 
-    rocprofv3 --kernel-trace --stats --output-format csv -d gpurun_out/prof/kt -o kt -- \
+    rocprofv3 --kernel-trace --stats --output-format csv -d $OUT/kt -o kt -- \
         python3 bench.py --workload W --steps 10 --warmup 2 --no-cpu-baseline --calibrate-copy
-    rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d gpurun_out/prof/fetch -o fetch -- \
+    rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d $OUT/fetch -o fetch -- \
         python3 bench.py --workload W --steps 3 --warmup 1 --no-cpu-baseline --calibrate-copy
-    rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d gpurun_out/prof/write -o write -- \
+    rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d $OUT/write -o write -- \
         python3 bench.py --workload W --steps 3 --warmup 1 --no-cpu-baseline --calibrate-copy
 
 Writes profiles/bload_workloadW_kernel_trace.md, profiles/bload_pack_workloadW_hbm_counters.md
@@ -69,8 +69,8 @@ def main() -> None:
 
     # ---- kernel trace
     lines = [f"# rocprofv3 kernel trace of bench.py, workload {cfg}", "",
-             "Command (MI355X box, repository root):", "",
-             "    rocprofv3 --kernel-trace --stats --output-format csv -d gpurun_out/prof/kt -o kt -- \\",
+             "Command (on the MI355X, from the repository root; OUT = a scratch directory):", "",
+             "    rocprofv3 --kernel-trace --stats --output-format csv -d $OUT/kt -o kt -- \\",
              f"        python3 bench.py --workload {w} --steps 10 --warmup 2 --no-cpu-baseline --calibrate-copy{flags}",
              "", "Summarised by `python -m paper_2310_10879_amd.profile_summary` from kt_kernel_stats.csv.", "",
              "| kernel | calls | avg ns | min ns | max ns | % of GPU time |", "|---|---|---|---|---|---|"]
@@ -117,10 +117,10 @@ def main() -> None:
         if name.startswith(pack_kernel):
             traffic = rd_b + wr_b
     out = [f"# rocprofv3 HBM counters of bench.py, workload {cfg}", "",
-           "Two counter passes, each a run of its own (MI355X box, repository root):", "",
-           "    rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d gpurun_out/prof/fetch -o fetch -- \\",
+           "Two counter passes, each a run of its own (on the MI355X, from the repository root; OUT = a scratch directory):", "",
+           "    rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d $OUT/fetch -o fetch -- \\",
            f"        python3 bench.py --workload {w} --steps 3 --warmup 1 --no-cpu-baseline --calibrate-copy",
-           "    rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d gpurun_out/prof/write -o write -- \\",
+           "    rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d $OUT/write -o write -- \\",
            f"        python3 bench.py --workload {w} --steps 3 --warmup 1 --no-cpu-baseline --calibrate-copy",
            "", "Mean per dispatch.  Scale factors from the calibration copy (known: 1048576 KiB read, 1048576 KiB",
            f"written): FETCH_SIZE x {f_scale:.5f}, WRITE_SIZE x {w_scale:.5f}.", ""] + rows
