@@ -3,17 +3,22 @@
 // per-slot form of the start table (BLoad, Methods section).
 //
 // The kernels are destination driven: a workgroup owns a contiguous piece of
-// the packed tensor (a "tile"), looks up which sequences land in it, stages
-// that short index table in LDS, and then streams 16-byte vectors from the
-// ragged source to the tile.  Every output byte is written by exactly one
-// thread, so no memset pass and no atomics are needed.
+// the packed tensor (a "tile"), looks up which sequences land in it, and
+// streams 16-byte vectors from the ragged source to the tile.  Every output
+// byte is written by exactly one thread, so no memset pass and no atomics are
+// needed.  A first pass (pack_locate_kernel) finds, for every tile, where in
+// the shuffled order its sequences begin.
 //
-// Two tile shapes:
-//   wide   (frame_bytes >= 512): a tile is a flat byte range of the packed
-//          tensor; each sequence overlapping it is one contiguous copy.
-//   narrow (frame_bytes <  512): a tile is 1024 consecutive slots; lanes take
-//          consecutive 16-byte destination vectors and assemble them from
-//          source elements of the widest type that divides the frame.
+// Two tile shapes (takes_wide_tiles chooses, from the frame size and the bytes
+// per sequence):
+//   wide   a tile is 4 KiB of the packed tensor, one 16-byte vector per thread;
+//          best where runs (a sequence's bytes) are long: a tile inside one run
+//          is a plain copy with wave-uniform scalar look-ups.  Frames of at
+//          least 64 bytes.
+//   narrow a tile is 1024 consecutive slots; the runs go into an LDS table,
+//          lanes take consecutive 16-byte destination vectors and assemble
+//          them from source elements of the widest type that divides the
+//          frame.  Small frames, and middle-sized frames of short sequences.
 #include "bload_common.hpp"
 
 #include <limits.h>
