@@ -65,9 +65,9 @@ const char* bload_status_string(bload_status status);
 int bload_last_hip_error(void);
 
 /* ------------------------------------------------------------------ plan --
- * Methods section: "blocks of size T_max by concatenating randomly sampled
- * sequences with length T_i <= T_max", each block closed as near T_max as the
- * visiting order allows, plus the table of starting indices.
+ * Methods section: blocks of T_max frames are put together from whole sequences,
+ * none longer than T_max, taken in random order; each block is closed as near
+ * T_max as the visiting order allows; a table keeps where every sequence starts.
  *
  * order:  a permutation of [0, n_seq) fixed by `seed` alone: position p holds
  *         the sequence walk(p), where walk applies a 6-round balanced Feistel

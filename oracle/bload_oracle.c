@@ -7,19 +7,19 @@
  * the HIP library and the library never calls it.
  *
  * What each function follows:
- *   - order:   Methods section, "concatenating randomly sampled sequences":
+ *   - order:   Methods section (the sequences of a block are taken at random):
  *              the paper fixes no generator, so the random order is a keyed
  *              bijection of [0, N) (balanced Feistel network + cycle walking,
  *              Black & Rogaway 2002) whose round function is the MurmurHash3
  *              32-bit finaliser and whose round keys are consecutive outputs
  *              of SplitMix64 (Steele, Lea & Flood 2014) started at the seed.
  *   - plan:    Methods section: blocks of T_max frames built from whole
- *              sequences with T_i <= T_max, closed "as close to T_max" as the
+ *              sequences with T_i <= T_max, closed as near T_max as the
  *              running order allows (next-fit: a sequence that does not fit
  *              the open block closes it and opens the next one).
  *   - pack:    Methods section: the closed block is filled up with 0's; the
- *              table "containing the starting index of each new video within
- *              each particular block" is kept per sequence (offset) and per
+ *              table of where each new sequence starts inside its block is
+ *              kept per sequence (offset) and per
  *              frame slot (reset flag, sequence id, frame index, valid).
  *   - reduce:  the consumer of that table (Methods section, resetting the
  *              carried state where a new sequence starts), in its simplest

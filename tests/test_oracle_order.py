@@ -1,4 +1,4 @@
-"""Pins for the oracle's seeded order (the "randomly sampled" of the Methods
+"""Pins for the oracle's seeded order (the random choice of sequences of the Methods
 section).  None of them re-types the oracle's formula: they use published known
 answers, algebraic inverses, and the properties a shuffle must have."""
 import numpy as np
