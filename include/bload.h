@@ -13,6 +13,11 @@
  *                         write the per-slot form of the start table
  *   bload_segment_reduce  per-sequence sum / mean over the packed blocks, using
  *                         only the packed tensor and that per-slot table
+ * and, around that path,
+ *   bload_plan_random_fit   the plan built with the sampler of the paper's pseudocode
+ *   bload_plan_shard        one data-parallel worker's share of a plan
+ *   bload_segment_scan      a recurrent consumer that drops its state at sequence starts
+ *   bload_strategy_counts   padding / frames deleted under the strategies the paper compares
  *
  * Conventions
  *   - Pointers named d_* are DEVICE pointers (hipMalloc-style memory of the
@@ -21,9 +26,10 @@
  *   - A frame is an opaque record of `frame_bytes` bytes (H*W*C*sizeof(elem));
  *     H and W are the same for all sequences of one call.
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the null stream).
- *     bload_pack and bload_segment_reduce only enqueue work on it;
- *     bload_plan enqueues, then waits for the stream, because it returns the
- *     block count to the host.
+ *     bload_pack, bload_segment_reduce and bload_segment_scan only enqueue work
+ *     on it (no synchronisation, no allocation: they can be recorded into a HIP
+ *     graph); the planners and bload_strategy_counts enqueue, then wait for the
+ *     stream, because they return counts to the host.
  *   - Every function returns a bload_status; nothing is thrown.  On any
  *     status other than BLOAD_OK the contents of the output buffers are
  *     unspecified (but nothing outside them is ever written).
