@@ -70,19 +70,25 @@ struct ReduceArgs {
 template <typename ElemT> struct Elem;
 template <> struct Elem<uint8_t> {
     typedef float Acc;
+    // a piece of a chunk holds fewer than 2^15 frames of at most 255: every float sum of
+    // them is a whole number below 2^24, i.e. exact, and needs no compensation
+    static constexpr bool kCompensate = false;
     __device__ static float get(uint8_t v) { return (float)v; }
 };
 struct half_bits { uint16_t bits; };           // IEEE binary16 storage
 template <> struct Elem<half_bits> {
     typedef float Acc;
+    static constexpr bool kCompensate = true;
     __device__ static float get(half_bits v) { return __half2float(__ushort_as_half(v.bits)); }
 };
 template <> struct Elem<float> {
     typedef float Acc;
+    static constexpr bool kCompensate = true;
     __device__ static float get(float v) { return v; }
 };
 template <> struct Elem<int32_t> {
     typedef long long Acc;
+    static constexpr bool kCompensate = false;
     __device__ static long long get(int32_t v) { return (long long)v; }
 };
 
@@ -101,6 +107,30 @@ template <typename Acc> struct OutOf;
 template <> struct OutOf<float> { typedef float T; };
 template <> struct OutOf<long long> { typedef long long T; };
 
+// A running sum that many terms are added to, one after the other.  Integers are
+// exact.  A float sum (COMPENSATED) carries the rounding error of every addition
+// along (Kahan's compensated summation), so that its error stays at about two
+// units in the last place of the sum of the |terms| however many there are,
+// instead of growing with their number.  Once the sum has left the finite range
+// the compensation is dropped, so that infinities add up as in plain arithmetic.
+template <typename Acc, bool COMPENSATED> struct Running {
+    Acc sum;
+    __device__ __forceinline__ void clear() { sum = 0; }
+    __device__ __forceinline__ void add(Acc term) { sum += term; }
+};
+template <> struct Running<float, true> {
+    float sum, lost;
+    __device__ __forceinline__ void clear() { sum = 0.0f; lost = 0.0f; }
+    __device__ __forceinline__ void add(float term)
+    {
+        const float y = term - lost;
+        const float t = sum + y;
+        const float l = (t - sum) - y;
+        lost = __builtin_isfinite(t) ? l : 0.0f;
+        sum = t;
+    }
+};
+
 template <typename Acc>
 __device__ __forceinline__ Acc finish(Acc sum, int32_t cnt, int mean)
 {
@@ -115,7 +145,8 @@ __device__ __forceinline__ float finish<float>(float sum, int32_t cnt, int mean)
 // ------------------------------------------------------------------- wide
 
 constexpr int kWideUnroll = 8;
-constexpr int kWideFlagBytes = 32768;      // LDS budget for the staged flags
+constexpr int kWideFlagBytes = 32768;      // LDS budget for the staged flags: also the longest chunk
+static_assert((int64_t)kWideFlagBytes * 255 < ((int64_t)1 << 24), "uint8 pieces must sum exactly in float");
 
 // First slot s in [t, len) whose staged flags say "valid" (WANT_VALID) or "not a
 // plain continuation: padding or a start flag" (!WANT_VALID); len if none.  The
@@ -272,12 +303,16 @@ __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
         scratch = reinterpret_cast<Acc*>(s_flags + flag_bytes) + (size_t)wave_id() * kWave * kScratchStride<Acc, VEC>();
     }
 
+    Running<Acc, Elem<ElemT>::kCompensate> run[VEC];
     Acc acc[VEC];
     ChunkDesc desc{kHeadNone, 0, 0, -1};
 
     // The chunk is a sequence of pieces: maximal runs of valid slots that hold
     // no start flag after their first slot.  Find a piece [t, e) from the
-    // staged flags, sum it with unconditional loads, hand the sum on.
+    // staged flags, sum it with unconditional loads, hand the sum on.  The
+    // frames of a piece are added eight at a time as a balanced tree, and the
+    // sums of the eights go into a compensated running sum: the float32 result
+    // is within a few units in the last place of sum |x| at any piece length.
     int32_t t = 0;
     for (;;) {
         t = next_slot<true, WAVE_ROW>(flags, t, len, a.row_lanes_log2);    // next valid slot
@@ -288,36 +323,41 @@ __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
         const bool head_open = t == 0 && !(flags[0] & 2) && (flags[-1] & 1);
         const int32_t e = next_slot<false, WAVE_ROW>(flags, t + 1, len, a.row_lanes_log2);  // padding or a start
 #pragma unroll
-        for (int k = 0; k < VEC; ++k) acc[k] = 0;
+        for (int k = 0; k < VEC; ++k) run[k].clear();
         const uint8_t* p = chunk_src + (int64_t)t * frame_bytes;          // frame of slot s, lane 0
         int32_t s = t;
+        static_assert(kWideUnroll == 8, "the tree below adds eight frames");
         for (; s + kWideUnroll <= e; s += kWideUnroll) {
             LaneData<ElemT, VEC> x[kWideUnroll];
 #pragma unroll
             for (int u = 0; u < kWideUnroll; ++u) x[u].load(p + (int64_t)u * frame_bytes + lane_off);
 #pragma unroll
-            for (int u = 0; u < kWideUnroll; ++u) {
+            for (int k = 0; k < VEC; ++k) {
+                Acc v[kWideUnroll];
 #pragma unroll
-                for (int k = 0; k < VEC; ++k) acc[k] += Elem<ElemT>::get(x[u].u.e[k]);
+                for (int u = 0; u < kWideUnroll; ++u) v[u] = Elem<ElemT>::get(x[u].u.e[k]);
+                run[k].add(((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7])));
             }
             p += (int64_t)kWideUnroll * frame_bytes;
         }
         if (s < e) {
             // the last, partial batch: all loads are issued at once as well (those
-            // past the piece re-read its last slot and are not added)
+            // past the piece re-read its last slot and count as 0)
             const int32_t left = e - s;
             LaneData<ElemT, VEC> x[kWideUnroll];
 #pragma unroll
             for (int u = 0; u < kWideUnroll; ++u)
                 x[u].load(p + (int64_t)min(u, left - 1) * frame_bytes + lane_off);
 #pragma unroll
-            for (int u = 0; u < kWideUnroll; ++u) {
-                if (u < left) {
+            for (int k = 0; k < VEC; ++k) {
+                Acc v[kWideUnroll];
 #pragma unroll
-                    for (int k = 0; k < VEC; ++k) acc[k] += Elem<ElemT>::get(x[u].u.e[k]);
-                }
+                for (int u = 0; u < kWideUnroll; ++u) v[u] = u < left ? Elem<ElemT>::get(x[u].u.e[k]) : (Acc)0;
+                run[k].add(((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7])));
             }
         }
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) acc[k] = run[k].sum;
         const int32_t cnt = e - t;
         // the segment ends here unless the piece runs to the chunk's end and the
         // slot after the chunk (flags[len], 0 past the block) continues it
@@ -536,7 +576,9 @@ __device__ __forceinline__ void narrow_load(const ReduceArgs& a, int64_t s0, int
 }
 
 // Hand one finished piece on: to the output row of its sequence, or to the
-// partial buffers when the tile border cuts its segment.
+// partial buffers when the tile border cuts its segment.  `slot` is the first
+// slot of the piece when the segment starts in this tile (`started`): the
+// sequence id is read there, as in the wide layout.
 template <typename Acc>
 __device__ __forceinline__ void narrow_emit(const ReduceArgs& a, int64_t q, int d, int64_t slot,
                                             bool is_end, bool started, Acc sum, int32_t cnt,
@@ -626,7 +668,7 @@ __global__ __launch_bounds__(kThreads) void reduce_narrow_kernel(ReduceArgs a)
                 const Acc sum = upto ? incl[j] : carry.sum + incl[j];
                 const int32_t start = upto ? pos0 + (31 - __clz((int)upto)) : seg.prev_start;
                 const int32_t cnt = start >= 0 ? pos0 + j - start + 1 : pos0 + j + 1;
-                narrow_emit<Acc>(a, q, d, s0 + j, is_end, start >= 0, sum, cnt, &s_desc);
+                narrow_emit<Acc>(a, q, d, g0 + max(start, 0), is_end, start >= 0, sum, cnt, &s_desc);
             }
         }
     }
@@ -700,7 +742,7 @@ __global__ __launch_bounds__(kThreads) void reduce_narrow_int_kernel(ReduceArgs 
             const Acc upto_end = prefix_before(pos0 + j + 1);
             const Acc sum = start >= 0 ? upto_end - prefix_before(start) : upto_end;
             const int32_t cnt = start >= 0 ? pos0 + j - start + 1 : pos0 + j + 1;
-            narrow_emit<Acc>(a, q, d, s0 + j, is_end, start >= 0, sum, cnt, &s_desc);
+            narrow_emit<Acc>(a, q, d, g0 + max(start, 0), is_end, start >= 0, sum, cnt, &s_desc);
         }
     }
     __syncthreads();
@@ -733,18 +775,20 @@ __global__ __launch_bounds__(kThreads) void reduce_stitch_kernel(ReduceArgs a, i
     if (first.cnt_tail <= 0 || d >= a.feat_dim) return;
     const Acc* head_part = static_cast<const Acc*>(a.head_part);
     const Acc* tail_part = static_cast<const Acc*>(a.tail_part);
-    Acc sum = tail_part[q * a.feat_dim + d];
+    Running<Acc, sizeof(Acc) == 4> sum;
+    sum.clear();
+    sum.add(tail_part[q * a.feat_dim + d]);
     int64_t cnt = first.cnt_tail;
     for (int64_t q2 = q + 1; q2 < a.total_chunks; ++q2) {
         const ChunkDesc nd = a.desc[q2];
         if (nd.head_state == kHeadNone) break;
-        sum += head_part[q2 * a.feat_dim + d];
+        sum.add(head_part[q2 * a.feat_dim + d]);
         cnt += nd.cnt_head;
         if (nd.head_state != kHeadThrough) break;
     }
     if ((uint32_t)first.seq_tail < (uint32_t)a.n_seq)
         static_cast<Out*>(a.out)[(int64_t)first.seq_tail * a.feat_dim + d] =
-            finish<Acc>(sum, (int32_t)cnt, a.mean);
+            finish<Acc>(sum.sum, (int32_t)cnt, a.mean);
 }
 
 // ------------------------------------------------------------------- host

@@ -263,7 +263,8 @@ __global__ __launch_bounds__(kThreads) void scan_chain_kernel(ScanArgs a)
     for (int32_t c = 0; c < links; ++c) {
         const int64_t at = (block * links + c) * (int64_t)a.feat_dim + d;
         const float tail = a.carry[at];
-        handed = a.has_boundary[block * links + c] ? tail : a.decay_chunk * handed + tail;
+        // a state of exactly 0 stays 0 whatever decay^chunk is (it may have overflowed to inf)
+        handed = (a.has_boundary[block * links + c] || handed == 0.0f) ? tail : a.decay_chunk * handed + tail;
         a.carry[at] = handed;
     }
 }

@@ -27,3 +27,14 @@ def golden_rows(name):
 @pytest.fixture(scope="session")
 def golden():
     return golden_rows
+
+
+@pytest.fixture
+def progress(request):
+    """say(msg): print past pytest's output capture, so that a long test shows signs of life."""
+    capman = request.config.pluginmanager.getplugin("capturemanager")
+
+    def say(msg):
+        with capman.global_and_fixture_disabled():
+            print(msg, flush=True)
+    return say

@@ -1,5 +1,7 @@
 """Helpers shared by the GPU parity tests: upload seeded inputs, run the HIP
 library through its binding, bring results back as numpy."""
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import torch
 
@@ -89,3 +91,32 @@ def assert_packed_equal(out, ref, what=""):
             bad = np.argwhere(gn != r)
             raise AssertionError(f"{what}{name}: {len(bad)} mismatches, first at {bad[0].tolist()} "
                                  f"got {gn[tuple(bad[0])]} want {r[tuple(bad[0])]}")
+
+
+def assert_packed_equal_whole(out, src, so, L, ref_plan, frame_bytes, slab_blocks, what="", workers=8,
+                              say=print):
+    """Compare ALL blocks of a packed tensor (payload and the four planes of the start table)
+    with the oracle, slab by slab: the oracle packs blocks [lo, hi) on the host (several slabs
+    at a time on separate threads, each a call of its own), the slab is uploaded and compared
+    on the device.  Bounded host memory: `workers` slabs."""
+    B = ref_plan.num_blocks
+    slabs = [(lo, min(B, lo + slab_blocks)) for lo in range(0, B, slab_blocks)]
+
+    def make(rng):
+        return rng, oracle.pack_blocks(src, so, L, ref_plan, frame_bytes, rng[0], rng[1])
+
+    done = 0
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        # a bounded window of slabs in flight
+        for start in range(0, len(slabs), workers):
+            for (lo, hi), ref in ex.map(make, slabs[start:start + workers]):
+                got = (out.packed[lo:hi], out.seq_id[lo:hi], out.frame_idx[lo:hi], out.reset[lo:hi],
+                       out.valid[lo:hi])
+                same = all(torch.equal(g, torch.from_numpy(r).to(g.device)) for g, r in zip(got, ref))
+                if not same:
+                    binding_out = binding().Packed(*got)
+                    assert_packed_equal(binding_out, ref, f"{what}blocks {lo}:{hi}: ")
+                    raise AssertionError(f"{what}blocks {lo}:{hi} differ")
+                done += hi - lo
+            say(f"{what}{done} of {B} blocks equal to the oracle's")
+    assert done == B

@@ -1,72 +1,64 @@
 """The two largest workloads at full size, in the launch shapes the benchmark uses:
-plan compared whole, packed tensor compared on sampled blocks that the oracle packs one
-by one plus properties that hold at any size, reductions compared on sampled sequences."""
+plan, packed tensor, start table and every per-sequence reduction compared whole with the
+oracle (the packed tensor slab by slab), plus properties that hold at any size."""
 import numpy as np
 import pytest
 import torch
 
 import oracle
 from paper_2310_10879_amd import workloads
-from gpu_util import assert_packed_equal, assert_plan_equal, binding, gpu_plan, to_dev
+from gpu_util import assert_packed_equal_whole, assert_plan_equal, binding, gpu_plan, to_dev
 
 pytestmark = pytest.mark.gpu
 
 
-def sampled_blocks(ref_plan, L, rng, n_random=24):
-    B = ref_plan.num_blocks
-    picks = {0, B - 1, B // 2}
-    picks.update(int(b) for b in rng.integers(0, B, size=n_random))
-    # blocks of the longest and of some of the shortest sequences
-    picks.add(int(ref_plan.block_of_seq[int(np.argmax(L))]))
-    for i in np.argsort(L, kind="stable")[:4]:
-        picks.add(int(ref_plan.block_of_seq[int(i)]))
-    return sorted(picks)
-
-
-def check_reduction_on(idx, got_rows, src, so, L, D, dtype, op):
-    ref = oracle.segment_reduce(src, so[idx], L[idx], D, dtype, op)
+def check_reduction(got, src, so, L, D, dtype, op, say=print):
+    """Every row of the reduction against the oracle's (float64 accumulation over the ragged
+    source): |gpu - oracle| <= 1e-5 * max(|oracle|, A), A = mean |x| of the sequence (sum |x|
+    for sums).  A >= |oracle| always, so rows inside 1e-5 * |oracle| pass without A."""
+    ref = oracle.segment_reduce(src, so, L, D, dtype, op)
     if dtype == "i32":
-        assert np.array_equal(got_rows, ref)
+        assert np.array_equal(got, ref)
         return
-    for row, i in enumerate(idx):
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+    assert np.all(np.isfinite(got))
+    rows = np.nonzero((err > 1e-5 * np.abs(ref.astype(np.float64))).any(axis=1))[0]
+    say(f"reduction: {len(L) - len(rows)} rows inside 1e-5 * |oracle|, {len(rows)} need the "
+        f"sequence's own scale; largest error {err.max():.3g}")
+    for i in rows:
         seg = np.abs(src[so[i]:so[i] + L[i]].astype(np.float64)).sum(axis=0)
         scale = seg / L[i] if op == "mean" else seg
-        bound = 1e-5 * np.maximum(np.abs(ref[row].astype(np.float64)), scale)
-        err = np.abs(got_rows[row].astype(np.float64) - ref[row].astype(np.float64))
-        assert np.all(err <= bound), f"sequence {i}: max err {err.max()} bound {bound[np.argmax(err)]}"
+        bound = 1e-5 * np.maximum(np.abs(ref[i].astype(np.float64)), scale)
+        assert np.all(err[i] <= bound), f"sequence {i}: max err {err[i].max()} bound {bound[np.argmax(err[i])]}"
 
 
 @pytest.mark.parametrize("wid", [4, 5])
-def test_workload_full_size(wid):
+def test_workload_full_size(wid, progress):
     bl = binding()
     w = workloads.WORKLOADS[wid]
-    rng = np.random.default_rng(wid)
     L = workloads.lengths(wid)
     so = workloads.src_offsets(L)
-    print(f"workload {wid}: drawing {int(so[-1]) * w.frame_bytes / 1e9:.1f} GB of source", flush=True)
+    progress(f"workload {wid}: drawing {int(so[-1]) * w.frame_bytes / 1e9:.1f} GB of source")
     src = workloads.source(wid, 0, int(so[-1]), threads=16)
     N, T, F, D = w.n_seq, w.t_blk, w.frame_bytes, w.frame_elems
     seed = 0
     ref_plan = oracle.plan(L, T, oracle.order(N, seed))
-    print(f"workload {wid}: plan", flush=True)
+    progress(f"workload {wid}: plan")
     d_L = to_dev(L)
     plan_dev = gpu_plan(L, T, seed)
     assert_plan_equal(plan_dev, ref_plan, N)
     B = ref_plan.num_blocks
 
-    print(f"workload {wid}: upload + pack ({B} blocks)", flush=True)
+    progress(f"workload {wid}: upload + pack ({B} blocks)")
     d_src = torch.from_numpy(src.view(np.uint8).reshape(-1)).to("cuda:0")
     out = bl.bload_pack(d_src, to_dev(so), d_L, plan_dev, F)
     torch.cuda.synchronize()
 
-    print(f"workload {wid}: sampled blocks", flush=True)
-    for b in sampled_blocks(ref_plan, L, rng):
-        ref = oracle.pack_blocks(src, so, L, ref_plan, F, b, b + 1)
-        got = bl.Packed(out.packed[b:b + 1], out.seq_id[b:b + 1], out.frame_idx[b:b + 1],
-                        out.reset[b:b + 1], out.valid[b:b + 1])
-        assert_packed_equal(got, ref, f"workload {wid} block {b}: ")
+    progress(f"workload {wid}: every block against the oracle")
+    assert_packed_equal_whole(out, src, so, L, ref_plan, F, 256 if wid == 4 else 4096,
+                              f"workload {wid}: ", say=progress)
 
-    print(f"workload {wid}: whole-tensor properties", flush=True)
+    progress(f"workload {wid}: whole-tensor properties")
     valid = out.valid.view(-1).bool()
     assert int(valid.sum().item()) == int(so[-1])                     # every frame has a slot
     assert int(out.reset.sum(dtype=torch.int64).item()) == N          # one start per sequence
@@ -95,15 +87,8 @@ def test_workload_full_size(wid):
         nz = (words[lo:hi] != 0).any(dim=1)
         assert not bool((nz & ~valid[lo:hi]).any().item()), f"non-zero padding in slots {lo}:{hi}"
 
-    print(f"workload {wid}: reduce", flush=True)
+    progress(f"workload {wid}: reduce")
     red = bl.bload_segment_reduce(out.packed, out.seq_id, out.reset, out.valid, B, T, D, w.dtype,
                                   w.op, N)
     torch.cuda.synchronize()
-    if wid == 5:
-        ref = oracle.segment_reduce(src, so, L, D, w.dtype, w.op)
-        assert np.array_equal(red.cpu().numpy(), ref)
-    else:
-        idx = np.unique(np.concatenate([rng.integers(0, N, size=1500), np.argsort(L)[-20:],
-                                        np.argsort(L)[:20], [0, N - 1]]))
-        check_reduction_on(idx, red[torch.from_numpy(idx).to("cuda:0")].cpu().numpy(), src, so, L,
-                           D, w.dtype, w.op)
+    check_reduction(red.cpu().numpy(), src, so, L, D, w.dtype, w.op, say=progress)

@@ -149,6 +149,75 @@ def test_reduce_workloads_full_size(wid):
     check_reduction(red.cpu().numpy(), src, so, L, w.frame_elems, w.dtype, w.op)
 
 
+# ---- float32 sums that are accurate by construction, not by the luck of random rounding
+
+U = 2.0 ** -24          # unit roundoff of float32
+
+
+def same_sign_source(rng, total, D):
+    """Positive float32 values over six decades, every 97th frame a huge one in front of
+    thousands of small ones: a single float32 accumulator per feature loses the small terms
+    (error ~ n/2 units in the last place of the sum), which is what must not happen."""
+    x = np.exp(rng.uniform(np.log(1e-3), np.log(1e3), size=(total, D))).astype(np.float32)
+    x[::97] *= np.float32(4096.0)
+    return x
+
+
+def assert_sum_accuracy(got, src, so, L, D, op, ulps):
+    """Against the float64 oracle: inside the 1e-5 bar, and inside `ulps` units of float32
+    roundoff of sum |x| (what the summation scheme guarantees at any length)."""
+    ref = oracle.segment_reduce(src, so, L, D, "f32", op).astype(np.float64)
+    scale = np.add.reduceat(np.abs(src.astype(np.float64)), so[:-1], axis=0)
+    if op == "mean":
+        scale = scale / L[:, None]
+    err = np.abs(got.astype(np.float64) - ref)
+    assert np.all(err <= REL_TOL * np.maximum(np.abs(ref), scale)), f"max relative error {np.max(err / scale)}"
+    assert np.all(err <= ulps * U * scale), f"{np.max(err / (U * scale)):.1f} units of roundoff, allowed {ulps}"
+
+
+@pytest.mark.parametrize("n,T,D,ulps", [(48, 3000, 80, 12),      # lanes across features, many chunks + stitch
+                                        (300, 3000, 80, 12),     # fewer chunks per block
+                                        (6, 3000, 2048, 12),     # a wave per row
+                                        (40, 30000, 1, 32),      # lanes across time, 15 tiles per sequence
+                                        (64, 3000, 3, 32)])
+@pytest.mark.parametrize("op", ["sum", "mean"])
+def test_reduce_float32_sums_hold_at_any_length(n, T, D, ulps, op):
+    bl = binding()
+    rng = np.random.default_rng(T + D)
+    L = np.full(n, T, dtype=np.int32)                 # every sequence fills a block
+    so = workloads.src_offsets(L)
+    src = same_sign_source(rng, int(so[-1]), D)
+    pl = oracle.plan(L, T, oracle.order(n, 3))
+    packed, seq_id, _, reset, valid = oracle.pack(src, so, L, pl, D * 4)
+    out = bl.bload_segment_reduce(to_dev(packed), to_dev(seq_id), to_dev(reset), to_dev(valid),
+                                  pl.num_blocks, T, D, "f32", op, n)
+    assert_sum_accuracy(out.cpu().numpy(), src, so, L, D, op, ulps)
+
+
+def test_reduce_float32_one_chunk_per_block_of_3000_frames():
+    """8192 blocks of one 3000-frame sequence of 80 float32 features: enough blocks that every
+    block is one chunk, so a sequence is summed by one row of lanes from end to end (the launch
+    shape of the largest workload).  The payload is drawn on the device; the oracle sums sampled
+    sequences copied back from it."""
+    bl = binding()
+    B, T, D = 8192, 3000, 80
+    assert bl.bload_segment_reduce_workspace_bytes(B, T, D, "f32") == 0       # no chunk borders
+    g = torch.Generator(device="cuda:0").manual_seed(5)
+    x = torch.empty((B, T, D), dtype=torch.float32, device="cuda:0")
+    x.uniform_(float(np.log(1e-3)), float(np.log(1e3)), generator=g).exp_()
+    x[:, ::97] *= 4096.0
+    seq_id = torch.arange(B, dtype=torch.int32, device="cuda:0")[:, None].expand(B, T).contiguous()
+    valid = torch.ones((B, T), dtype=torch.uint8, device="cuda:0")
+    reset = torch.zeros((B, T), dtype=torch.uint8, device="cuda:0")
+    reset[:, 0] = 1
+    out = bl.bload_segment_reduce(x, seq_id, reset, valid, B, T, D, "f32", "mean", B)
+    pick = np.unique(np.concatenate([[0, B - 1], np.random.default_rng(1).integers(0, B, size=62)]))
+    src = x[torch.from_numpy(pick).to("cuda:0")].cpu().numpy().reshape(-1, D)
+    L = np.full(len(pick), T, dtype=np.int32)
+    assert_sum_accuracy(out[torch.from_numpy(pick).to("cuda:0")].cpu().numpy(), src,
+                        workloads.src_offsets(L), L, D, "mean", 12)
+
+
 # ---- arbitrary flags: the consumer's rule, not only what a correct pack writes
 
 def random_flags(rng, B, T, p_valid, p_reset):
