@@ -110,7 +110,7 @@ def main() -> int:
         share, local_frames, local_seqs = plan, total_frames, N
     B = share.num_blocks
     packed = bload.alloc_packed(B, T, F, dev)
-    pack_ws = torch.empty(max(16, bload.bload_pack_workspace_bytes(B, T, F)), dtype=torch.uint8,
+    pack_ws = torch.empty(max(32, bload.bload_pack_workspace_bytes(N, B, T, F)), dtype=torch.uint8,
                           device=dev)
     red_ws = torch.empty(max(16, bload.bload_segment_reduce_workspace_bytes(B, T, D, w.dtype)),
                          dtype=torch.uint8, device=dev)

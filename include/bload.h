@@ -18,6 +18,7 @@
  *   bload_plan_shard        one data-parallel worker's share of a plan
  *   bload_segment_scan      a recurrent consumer that drops its state at sequence starts
  *   bload_strategy_counts   padding / frames deleted under the strategies the paper compares
+ *   bload_pack_check        are these tables a plan bload_pack can take
  *
  * Conventions
  *   - Pointers named d_* are DEVICE pointers (hipMalloc-style memory of the
@@ -54,8 +55,9 @@ typedef enum {
                               unknown dtype / op, or an unsupported dtype-op pair */
     BLOAD_ELENGTH = 2,     /* some L_i < 1 or L_i > t_blk (the method needs T_i <= T_max) */
     BLOAD_EWORKSPACE = 3,  /* workspace smaller than the *_workspace_bytes() answer */
-    BLOAD_EALIGN = 4,      /* a payload / workspace base is not 16-byte aligned, or an
-                              int32 / int64 table is not naturally aligned */
+    BLOAD_EALIGN = 4,      /* a payload / workspace base is not 16-byte aligned (32-byte for
+                              bload_pack's workspace), or an int32 / int64 table is not
+                              naturally aligned */
     BLOAD_EOVERFLOW = 5,   /* n_seq or num_blocks * t_blk beyond the supported range */
     BLOAD_EHIP = 6         /* a HIP runtime call failed (bload_last_hip_error() says which) */
 } bload_status;
@@ -197,13 +199,17 @@ bload_status bload_plan_shard(const int32_t* d_order, const int32_t* d_block_of_
  *                     (all five outputs 16-byte aligned)
  *
  * d_workspace         device scratch of >= bload_pack_workspace_bytes(...) bytes,
- *                     16-byte aligned (one int32 per destination tile -- 4 KiB of
- *                     packed tensor when frame_bytes >= 512, else 1024 slots --
- *                     saying where the tile starts in the shuffled order);
- *                     contents meaningless afterwards
+ *                     32-byte aligned: one 32-byte record per sequence (where it
+ *                     lands, where it comes from) and one int32 per destination
+ *                     tile -- 4 KiB of packed tensor or 1024 slots -- saying where
+ *                     the tile starts in the shuffled order; contents meaningless
+ *                     afterwards
  *
  * Every byte of the five outputs is written exactly once (no prior memset is
- * needed).  Asynchronous on `hip_stream`.  n_seq = 0 / num_blocks = 0: no-op.
+ * needed), and nothing outside them whatever the tables hold.  The tables are
+ * trusted otherwise: tables that are not a plan give a meaningless result, and
+ * source offsets outside the source are read; bload_pack_check tells.
+ * Asynchronous on `hip_stream`.  n_seq = 0 / num_blocks = 0: no-op.
  */
 /* Which of its two kernels bload_pack launches for these sizes: 4096 when the packed
  * tensor is cut into tiles of 4096 bytes (pack_wide_kernel), 0 when it is cut into
@@ -212,7 +218,7 @@ bload_status bload_plan_shard(const int32_t* d_order, const int32_t* d_block_of_
 int32_t bload_pack_tile_bytes(int64_t n_seq, int64_t num_blocks, int32_t t_blk, int64_t frame_bytes,
                               int32_t src_aligned_16);
 
-size_t bload_pack_workspace_bytes(int64_t num_blocks, int32_t t_blk, int64_t frame_bytes);
+size_t bload_pack_workspace_bytes(int64_t n_seq, int64_t num_blocks, int32_t t_blk, int64_t frame_bytes);
 
 bload_status bload_pack(const void* d_src, const int64_t* d_src_offsets, const int32_t* d_lengths,
                         const int32_t* d_order, const int32_t* d_block_of_seq,
@@ -221,6 +227,28 @@ bload_status bload_pack(const void* d_src, const int64_t* d_src_offsets, const i
                         void* d_packed, int32_t* d_seq_id, int32_t* d_frame_idx,
                         uint8_t* d_reset, uint8_t* d_valid,
                         void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Methods section: whole sequences, one after another from the block's first
+ * slot, none split, none beyond the block's end.  This call verifies that the
+ * tables handed to bload_pack describe such a layout, without packing anything:
+ *   - block_first[0 .. num_blocks] is non-decreasing, starts at 0 and ends at
+ *     P <= n_seq; every position p < P holds a sequence index in [0, n_seq);
+ *   - the sequence at position p lies in the block whose range contains p, at
+ *     offset 0 if it is the block's first and right behind its predecessor
+ *     otherwise, and ends at or before slot t_blk;
+ *   - 1 <= L_i, and the source range [src_offsets[i], src_offsets[i] + L_i) lies
+ *     inside [0, total_frames) and src_offsets[i+1] - src_offsets[i] = L_i,
+ * for every sequence listed.  (Together these make the listed sequences distinct.)
+ * BLOAD_OK if so, BLOAD_EINVAL if not; *h_first_bad (may be NULL) receives the
+ * smallest shuffled position or block at which a rule fails, -1 if none.
+ * d_workspace: >= 16 bytes, 16-byte aligned.  Synchronises the stream.
+ */
+bload_status bload_pack_check(const int64_t* d_src_offsets, const int32_t* d_lengths,
+                              const int32_t* d_order, const int32_t* d_block_of_seq,
+                              const int32_t* d_offset_of_seq, const int32_t* d_block_first,
+                              int64_t n_seq, int64_t num_blocks, int32_t t_blk, int64_t total_frames,
+                              int64_t* h_first_bad, void* d_workspace, size_t workspace_bytes,
+                              void* hip_stream);
 
 /* -------------------------------------------------------- segment reduce --
  * Methods section: knowing where a new sequence starts lets the consumer drop
@@ -234,9 +262,12 @@ bload_status bload_pack(const void* d_src, const int64_t* d_src_offsets, const i
  * d_out      out  [n_seq, feat_dim]: float32 for U8 / F16 / F32 inputs (float32
  *                 accumulation over chunks of time, chunks added in time order),
  *                 int64 for I32 (exact).  MEAN divides by the segment's frame
- *                 count; I32 supports SUM only.  Row i is written iff some
- *                 valid segment carries seq_id i; ids outside [0, n_seq) are
- *                 skipped.
+ *                 count; I32 supports SUM only.  A segment's row is d_seq_id at
+ *                 its first slot: row i is written iff some segment starts with
+ *                 seq_id i; ids outside [0, n_seq) are skipped.  float32 sums are
+ *                 compensated: whatever the length of a sequence, the result is
+ *                 within a few units of float32 roundoff of sum |x| (exact for U8
+ *                 while the sum stays below 2^24).
  * d_workspace     device scratch of >= bload_segment_reduce_workspace_bytes(...)
  *                 bytes, 16-byte aligned.
  *

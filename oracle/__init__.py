@@ -84,6 +84,9 @@ def _load():
         lib.bload_oracle_chunk_sampling.restype = None
         lib.bload_oracle_chunk_sampling.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
                                                     ctypes.c_void_p, ctypes.c_void_p]
+        lib.bload_oracle_plan_check.restype = ctypes.c_int64
+        lib.bload_oracle_plan_check.argtypes = [ctypes.c_void_p] * 6 + [ctypes.c_int64, ctypes.c_int64,
+                                                                       ctypes.c_int32, ctypes.c_int64]
         _lib = lib
     return _lib
 
@@ -302,3 +305,16 @@ def segment_scan_packed(packed, reset, valid, feat_dim: int, dtype: str, decay: 
     if rc != 0:
         raise ValueError("unsupported dtype")
     return out, scale
+
+
+def plan_check(src_offsets, lengths, order_, block_of_seq, offset_of_seq, block_first, num_blocks: int,
+               t_blk: int, total_frames: int) -> int:
+    """-1 if the tables describe blocks of whole sequences laid one after another, else the
+    smallest block / shuffled position at which they do not.  ``block_first`` needs at least
+    num_blocks + 1 entries."""
+    so = _c(src_offsets, np.int64)
+    L, o = _c(lengths, np.int32), _c(order_, np.int32)
+    bo, oo, bf = _c(block_of_seq, np.int32), _c(offset_of_seq, np.int32), _c(block_first, np.int32)
+    assert bf.shape[0] >= num_blocks + 1 and so.shape[0] == L.shape[0] + 1
+    return int(_load().bload_oracle_plan_check(_p(so), _p(L), _p(o), _p(bo), _p(oo), _p(bf), L.shape[0],
+                                               num_blocks, t_blk, total_frames))

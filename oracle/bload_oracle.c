@@ -29,12 +29,16 @@
  *              and Table 1 ("padding amount").
  *   - shard:   Problem Statement: equal sample counts for all data-parallel workers.
  *   - random fit: the sampler named in the caption of the pseudocode figure.
+ *   - plan check: Methods section: a block is whole sequences laid one after
+ *              another from its first slot, none beyond its end.
  *
  * Parity pins (tests/test_oracle_*.py): SplitMix64 known answers, invertible
  * finaliser, bijectivity and spread of the order; next-fit invariants, closed
  * forms and a brute-force optimum on tiny inputs; frame-exactly-once decoding
  * of a tagged payload; reductions of payloads with closed-form sums; the
- * paper's printed pad-to-longest count.  The identity of the permutation (which
+ * paper's printed pad-to-longest count; the plan check accepts every plan the
+ * planners make and is compared with a cell-by-cell simulation of the layout on
+ * corrupted tables.  The identity of the permutation (which
  * bijection a seed gives) is a free choice of this implementation: "parity unpinned"
  * beyond those properties.
  */
@@ -540,4 +544,55 @@ int bload_oracle_segment_scan_packed(const void* packed, const uint8_t* reset, c
         }
     }
     return 0;
+}
+
+/* ------------------------------------------------------------- plan check */
+
+/* Do the tables describe blocks made of whole sequences laid one after another
+ * (Methods section)?  Index k is tested as a block (k < num_blocks) and as a
+ * shuffled position (k < block_first[num_blocks]); the smallest k at which a
+ * rule fails is returned, -1 if none does.
+ *   block k:     0 <= block_first[k] <= block_first[k+1] <= n, block_first[0] = 0
+ *   position k:  i = order[k] is a sequence; 1 <= L_i; it starts at slot
+ *                offset_of_seq[i] >= 0 of block block_of_seq[i] and ends at or
+ *                before slot t_blk; k lies in that block's range of positions;
+ *                the block's first sequence starts at slot 0, every other one
+ *                where the sequence before it ends; its source frames
+ *                [src_offsets[i], src_offsets[i] + L_i) lie inside the source and
+ *                src_offsets[i+1] = src_offsets[i] + L_i. */
+int64_t bload_oracle_plan_check(const int64_t* src_offsets, const int32_t* lengths,
+                                const int32_t* order, const int32_t* block_of_seq,
+                                const int32_t* offset_of_seq, const int32_t* block_first,
+                                int64_t n, int64_t num_blocks, int32_t t_blk, int64_t total_frames)
+{
+    if (n <= 0 || num_blocks <= 0) return -1;
+    int64_t listed = block_first[num_blocks];
+    if (listed < 0) listed = 0;
+    if (listed > n) listed = n;
+    int64_t last = num_blocks > listed ? num_blocks : listed;
+    for (int64_t k = 0; k < last; ++k) {
+        if (k < num_blocks) {
+            int64_t lo = block_first[k], hi = block_first[k + 1];
+            if (lo < 0 || hi < lo || hi > n) return k;
+            if (k == 0 && lo != 0) return k;
+        }
+        if (k < listed) {
+            int64_t i = order[k];
+            if (i < 0 || i >= n) return k;
+            int64_t len = lengths[i], off = offset_of_seq[i], b = block_of_seq[i];
+            if (len < 1 || off < 0 || off + len > t_blk) return k;
+            if (src_offsets[i] < 0 || src_offsets[i] + len > total_frames) return k;
+            if (src_offsets[i + 1] != src_offsets[i] + len) return k;
+            if (b < 0 || b >= num_blocks) return k;
+            if (block_first[b] < 0 || k < block_first[b] || k >= block_first[b + 1]) return k;
+            if (k == block_first[b]) {
+                if (off != 0) return k;
+            } else {
+                int64_t before = order[k - 1];
+                if (before < 0 || before >= n) return k;
+                if (off != (int64_t)offset_of_seq[before] + (int64_t)lengths[before]) return k;
+            }
+        }
+    }
+    return -1;
 }

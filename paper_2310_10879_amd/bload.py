@@ -50,12 +50,15 @@ _lib.bload_plan_shard.restype = ctypes.c_int
 _lib.bload_plan_shard.argtypes = [_vp, _vp, _vp, _i64, _i64, _i32, _i32, _vp, _vp, _vp,
                                   ctypes.POINTER(_i64), ctypes.POINTER(_i64), _vp, _sz, _vp]
 _lib.bload_pack_workspace_bytes.restype = _sz
-_lib.bload_pack_workspace_bytes.argtypes = [_i64, _i32, _i64]
+_lib.bload_pack_workspace_bytes.argtypes = [_i64, _i64, _i32, _i64]
 _lib.bload_pack_tile_bytes.restype = _i32
 _lib.bload_pack_tile_bytes.argtypes = [_i64, _i64, _i32, _i64, _i32]
 _lib.bload_pack.restype = ctypes.c_int
 _lib.bload_pack.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i32, _i64,
                             _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.bload_pack_check.restype = ctypes.c_int
+_lib.bload_pack_check.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i32, _i64,
+                                  ctypes.POINTER(_i64), _vp, _sz, _vp]
 
 
 class StrategyCounts(ctypes.Structure):
@@ -121,8 +124,8 @@ def bload_plan_workspace_bytes(n_seq: int) -> int:
     return int(_lib.bload_plan_workspace_bytes(n_seq))
 
 
-def bload_pack_workspace_bytes(num_blocks: int, t_blk: int, frame_bytes: int) -> int:
-    return int(_lib.bload_pack_workspace_bytes(num_blocks, t_blk, frame_bytes))
+def bload_pack_workspace_bytes(n_seq: int, num_blocks: int, t_blk: int, frame_bytes: int) -> int:
+    return int(_lib.bload_pack_workspace_bytes(n_seq, num_blocks, t_blk, frame_bytes))
 
 
 def bload_segment_reduce_workspace_bytes(num_blocks: int, t_blk: int, feat_dim: int,
@@ -254,8 +257,8 @@ def bload_pack(src: torch.Tensor, src_offsets: torch.Tensor, lengths: torch.Tens
             out.seq_id.numel() != plan.num_blocks * plan.t_blk:
         raise ValueError("output buffers do not match num_blocks * t_blk")
     if workspace is None:
-        need = bload_pack_workspace_bytes(plan.num_blocks, plan.t_blk, frame_bytes)
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=lengths.device)
+        need = bload_pack_workspace_bytes(n, plan.num_blocks, plan.t_blk, frame_bytes)
+        workspace = torch.empty(max(need, 32), dtype=torch.uint8, device=lengths.device)
     st = _lib.bload_pack(_ptr(src), _ptr(src_offsets, torch.int64), _ptr(lengths, torch.int32),
                          _ptr(plan.order, torch.int32), _ptr(plan.block_of_seq, torch.int32),
                          _ptr(plan.offset_of_seq, torch.int32), _ptr(plan.block_first, torch.int32),
@@ -266,6 +269,24 @@ def bload_pack(src: torch.Tensor, src_offsets: torch.Tensor, lengths: torch.Tens
                          workspace.numel() * workspace.element_size(), _stream())
     _check(st)
     return out
+
+
+def bload_pack_check(src_offsets: torch.Tensor, lengths: torch.Tensor, plan: Plan,
+                     total_frames: int | None = None) -> int:
+    """-1 if the tables are a plan ``bload_pack`` can take, else the smallest shuffled position
+    or block at which they are not.  Synchronises the current stream."""
+    ws = torch.empty(16, dtype=torch.uint8, device=lengths.device)
+    bad = _i64(-1)
+    st = _lib.bload_pack_check(_ptr(src_offsets, torch.int64), _ptr(lengths, torch.int32),
+                               _ptr(plan.order, torch.int32), _ptr(plan.block_of_seq, torch.int32),
+                               _ptr(plan.offset_of_seq, torch.int32), _ptr(plan.block_first, torch.int32),
+                               lengths.shape[0], plan.num_blocks, plan.t_blk,
+                               plan.total_frames if total_frames is None else total_frames,
+                               ctypes.byref(bad), _ptr(ws), 16, _stream())
+    if st == EINVAL and bad.value >= 0:
+        return int(bad.value)
+    _check(st)
+    return -1
 
 
 def bload_segment_reduce(packed: torch.Tensor, seq_id: torch.Tensor, reset: torch.Tensor,

@@ -6,8 +6,11 @@
 // the packed tensor (a "tile"), looks up which sequences land in it, and
 // streams 16-byte vectors from the ragged source to the tile.  Every output
 // byte is written by exactly one thread, so no memset pass and no atomics are
-// needed.  A first pass (pack_locate_kernel) finds, for every tile, where in
-// the shuffled order its sequences begin.
+// needed.  A first pass (pack_prepare_kernel) turns the plan into a table of
+// "runs" in shuffled order -- one 32-byte record per sequence saying where it
+// lands and where it comes from, so that the copy kernels need one contiguous
+// read per sequence instead of a chain of look-ups through five tables -- and
+// finds, for every tile, where in that table its runs begin.
 //
 // Two tile shapes (takes_wide_tiles chooses, from the frame size and the bytes
 // per sequence):
@@ -25,14 +28,24 @@
 
 namespace bload {
 
+// Where one sequence goes: the record the copy kernels work from.  Position p of the
+// table belongs to shuffled position p; slots are numbered globally (block * T_blk +
+// slot in block).  A position that holds no sequence (a worker's share lists only its
+// own) has dst = INT64_MAX, which also ends the list.
+struct __attribute__((aligned(32))) Run {
+    int64_t dst;       // first slot
+    int64_t src;       // first source frame
+    int32_t len;       // frames
+    int32_t seq;       // original sequence index
+    int32_t block;     // dst / T_blk
+    int32_t pad_;
+};
+static_assert(sizeof(Run) == 32, "a run is two 16-byte vectors");
+constexpr int64_t kNoRun = INT64_MAX;
+
 struct PackArgs {
     const uint8_t* src;
-    const int64_t* src_offsets;
-    const int32_t* lengths;
-    const int32_t* order;
-    const int32_t* block_of_seq;
-    const int32_t* offset_of_seq;
-    const int32_t* block_first;
+    const Run* runs;          // [n_seq], by shuffled position
     int32_t n_seq;
     int32_t t_blk;
     int64_t frame_bytes;
@@ -57,8 +70,8 @@ struct RunTable {
 };
 
 // Fill `tab` with the runs that can overlap global slots [gs_lo, gs_hi), reading
-// the shuffled order forward from position `first` (the tile's entry of the
-// locate pass: the last position of the tile's first block that starts at or
+// the run table forward from position `first` (the tile's entry of the
+// prepare pass: the last position of the tile's first block that starts at or
 // before gs_lo).  Called by the whole workgroup, one candidate position per
 // participating thread and step; runs are sorted by destination, so the runs to keep are a
 // prefix of the candidates and candidate k becomes table entry k.  Ends with
@@ -79,23 +92,22 @@ __device__ __forceinline__ void gather_runs(const PackArgs& a, int32_t first, in
         const int64_t q = (int64_t)first + k;
         bool take = false;
         if (tid < width && q < n_seq && k < MAXRUNS) {
-            const uint32_t i = (uint32_t)a.order[q];
-            if (i < (uint32_t)n_seq) {
-                const int64_t g = (int64_t)a.block_of_seq[i] * a.t_blk + a.offset_of_seq[i];
-                take = g < gs_hi;
-                if (take) {
-                    tab.src[k] = a.src_offsets[i];
-                    tab.dst[k] = (int32_t)(g - gs_lo);
-                    tab.len[k] = a.lengths[i];
-                    tab.seq[k] = (int32_t)i;
-                }
+            const Run r = a.runs[q];
+            take = r.dst < gs_hi;
+            if (take) {
+                tab.src[k] = r.src;
+                tab.dst[k] = (int32_t)(r.dst - gs_lo);
+                tab.len[k] = r.len;
+                tab.seq[k] = r.seq;
             }
         }
-        // the first candidate that is not kept ends the table
-        const uint64_t refuse = __ballot(tid < width && !take);
+        // the first candidate that is not kept ends the table.  Whether any was refused comes
+        // out of the barrier itself (every wave sees the same answer, whatever a faster wave
+        // does to tab.n in its next step).
+        const bool refused = tid < width && !take;
+        const uint64_t refuse = __ballot(refused);
         if (refuse && lane_id() == __ffsll((unsigned long long)refuse) - 1) atomicMin(&tab.n, k);
-        __syncthreads();
-        if (tab.n != INT_MAX) break;
+        if (__syncthreads_or(refused ? 1 : 0)) break;
     }
     if (tid == 0) {
         const int32_t n = min(tab.n, MAXRUNS);
@@ -211,37 +223,55 @@ __device__ __forceinline__ void write_slots(const PackArgs& a, int64_t lo, int64
 }
 
 // Pass 1 (used by both tile shapes, which come after it in this file's launch
-// order): for every tile, the last shuffled position of the tile's first block
-// whose sequence starts at or before the tile's first slot (the block's first
-// sequence starts at slot 0, so there is one).  One thread per tile.
-__global__ __launch_bounds__(kThreads) void pack_locate_kernel(
-    const int32_t* __restrict__ order, const int32_t* __restrict__ offset_of_seq,
-    const int32_t* __restrict__ block_first, int32_t n_seq, int64_t t_blk, int64_t frame_bytes,
-    int64_t n_tiles, int32_t tile_bytes, double inv_frame_bytes, double inv_t_blk,
+// order).  Thread p < n_seq writes the run of shuffled position p.  Thread t < n_tiles
+// finds, for tile t, the last shuffled position of the tile's first block whose
+// sequence starts at or before the tile's first slot (the block's first sequence
+// starts at slot 0, so there is one); it searches the plan's own tables, so the two
+// halves do not depend on each other.
+__global__ __launch_bounds__(kThreads) void pack_prepare_kernel(
+    const int64_t* __restrict__ src_offsets, const int32_t* __restrict__ lengths,
+    const int32_t* __restrict__ order, const int32_t* __restrict__ block_of_seq,
+    const int32_t* __restrict__ offset_of_seq, const int32_t* __restrict__ block_first,
+    int32_t n_seq, int64_t num_blocks, int64_t t_blk, int64_t frame_bytes, int64_t n_tiles,
+    int32_t tile_bytes, double inv_frame_bytes, double inv_t_blk, Run* __restrict__ runs,
     int32_t* __restrict__ first_pos)
 {
-    const int64_t tile = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (tile >= n_tiles) return;
-    const int64_t gs_lo = floor_div(tile * tile_bytes, frame_bytes, inv_frame_bytes);
-    const int64_t b0 = floor_div(gs_lo, t_blk, inv_t_blk);
-    const int32_t rel = (int32_t)(gs_lo - b0 * t_blk);
-    int32_t p = min(max(block_first[b0], 0), n_seq);
-    int32_t above = min(max(block_first[b0 + 1], p), n_seq);
-    while (above - p > 1) {
-        const int32_t mid = p + ((above - p) >> 1);
-        const uint32_t i = (uint32_t)order[mid];
-        if (i < (uint32_t)n_seq && offset_of_seq[i] <= rel) p = mid; else above = mid;
+    const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (idx < n_seq) {
+        Run r{kNoRun, 0, 0, -1, -1, 0};
+        const uint32_t i = (uint32_t)order[idx];
+        if (i < (uint32_t)n_seq) {
+            const int64_t b = block_of_seq[i];
+            if (b >= 0 && b < num_blocks) {
+                r.dst = b * t_blk + offset_of_seq[i];
+                r.src = src_offsets[i];
+                r.len = lengths[i];
+                r.seq = (int32_t)i;
+                r.block = (int32_t)b;
+            }
+        }
+        runs[idx] = r;
     }
-    first_pos[tile] = p;
+    if (idx < n_tiles) {
+        const int64_t gs_lo = floor_div(idx * tile_bytes, frame_bytes, inv_frame_bytes);
+        const int64_t b0 = floor_div(gs_lo, t_blk, inv_t_blk);
+        const int32_t rel = (int32_t)(gs_lo - b0 * t_blk);
+        int32_t p = min(max(block_first[b0], 0), n_seq);
+        int32_t above = min(max(block_first[b0 + 1], p), n_seq);
+        while (above - p > 1) {
+            const int32_t mid = p + ((above - p) >> 1);
+            const uint32_t i = (uint32_t)order[mid];
+            if (i < (uint32_t)n_seq && offset_of_seq[i] <= rel) p = mid; else above = mid;
+        }
+        first_pos[idx] = p;
+    }
 }
 
-// Pass 2: the copy.  The lookup tables come as separate __restrict__ pointers
-// (not inside PackArgs) so that the compiler knows nothing this kernel stores
+// Pass 2: the copy.  The run table and the tiles' entries come as separate
+// __restrict__ pointers so that the compiler knows nothing this kernel stores
 // can alias them and keeps their loads on the scalar unit.
 __global__ __launch_bounds__(kThreads) void pack_wide_kernel(
-    PackArgs a, const int64_t* __restrict__ src_offsets, const int32_t* __restrict__ lengths,
-    const int32_t* __restrict__ order, const int32_t* __restrict__ block_of_seq,
-    const int32_t* __restrict__ offset_of_seq, const int32_t* __restrict__ first_pos,
+    PackArgs a, const Run* __restrict__ runs, const int32_t* __restrict__ first_pos,
     int32_t tile_bytes, double inv_frame_bytes)
 {
     const int64_t F = a.frame_bytes;
@@ -258,20 +288,20 @@ __global__ __launch_bounds__(kThreads) void pack_wide_kernel(
     // store per thread, plus the start-table entries of the few frames that
     // begin in the tile
     if (p < n_seq && tile_bytes == kThreads * 16) {
-        const uint32_t i = (uint32_t)order[p];
-        if (i < (uint32_t)n_seq) {
-            const int64_t g = (int64_t)block_of_seq[i] * T + offset_of_seq[i];
-            const int64_t len = lengths[i];
+        const Run r = runs[p];
+        if (r.dst != kNoRun) {
+            const int64_t g = r.dst;
+            const int64_t len = r.len;
             const int64_t run_lo = g * F;
             if (run_lo <= D0 && run_lo + len * F >= D0 + tile_bytes && D0 + tile_bytes <= total_bytes) {
-                const uint8_t* s = a.src + src_offsets[i] * F + (D0 - run_lo) + 16 * (int64_t)threadIdx.x;
+                const uint8_t* s = a.src + r.src * F + (D0 - run_lo) + 16 * (int64_t)threadIdx.x;
                 const vec16 x = __builtin_nontemporal_load(reinterpret_cast<const vec16_unaligned*>(s));
                 store_stream(reinterpret_cast<vec16*>(a.packed + D0) + threadIdx.x, x);
                 if (table_wave) {
                     // frames t of this run with D0 <= run_lo + t * F < D1
                     for (int64_t t = floor_div(D0 - run_lo + F - 1, F, inv_frame_bytes) + lane_id();
                          run_lo + t * F < D1 && t < len; t += kWave) {
-                        a.seq_id[g + t] = (int32_t)i;
+                        a.seq_id[g + t] = r.seq;
                         a.frame_idx[g + t] = (int32_t)t;
                         a.reset[g + t] = (uint8_t)(t == 0);
                         a.valid[g + t] = 1;
@@ -280,7 +310,7 @@ __global__ __launch_bounds__(kThreads) void pack_wide_kernel(
                 return;
             }
             // next most common: the tile lies in the zero tail of the run's block
-            if (run_lo + len * F <= D0 && ((int64_t)block_of_seq[i] + 1) * T * F >= D0 + tile_bytes) {
+            if (run_lo + len * F <= D0 && ((int64_t)r.block + 1) * T * F >= D0 + tile_bytes) {
                 const vec16 z = {0u, 0u, 0u, 0u};
                 store_stream(reinterpret_cast<vec16*>(a.packed + D0) + threadIdx.x, z);
                 if (table_wave) {
@@ -312,24 +342,23 @@ __global__ __launch_bounds__(kThreads) void pack_wide_kernel(
         int64_t cursor = D0;          // payload bytes written so far
         int64_t mcursor = m_lo;       // start-table slots written so far
         for (; p < n_seq; ++p) {
-            const uint32_t i = (uint32_t)order[p];
-            if (i >= (uint32_t)n_seq) break;
-            const int64_t g = (int64_t)block_of_seq[i] * T + offset_of_seq[i];
-            if (g >= gs_hi) break;
-            const int64_t len = lengths[i];
+            const Run r = runs[p];
+            const int64_t g = r.dst;
+            if (g >= gs_hi) break;                    // also the end of the list (kNoRun)
+            const int64_t len = r.len;
             if (g + len <= gs_lo) continue;           // ends before the tile: the tile starts in padding
             const int64_t run_lo = g * F;
             const int64_t lo = max(max(run_lo, D0), cursor);
             const int64_t hi = min(run_lo + len * F, D1);
             if (hi > lo) {
                 if (lo > cursor) write_range<true>(a.packed, cursor, lo, nullptr);
-                write_range<false>(a.packed, lo, hi, a.src + src_offsets[i] * F + (lo - run_lo));
+                write_range<false>(a.packed, lo, hi, a.src + r.src * F + (lo - run_lo));
                 cursor = hi;
             }
             if (table_wave) {
                 const int64_t s_lo = max(g, mcursor), s_hi = min(g + len, m_hi);
                 if (s_lo > mcursor) write_slots(a, mcursor, s_lo, -1, -1);
-                if (s_hi > s_lo) { write_slots(a, s_lo, s_hi, (int32_t)i, s_lo - g); mcursor = s_hi; }
+                if (s_hi > s_lo) { write_slots(a, s_lo, s_hi, r.seq, s_lo - g); mcursor = s_hi; }
             }
         }
         if (cursor < D1) write_range<true>(a.packed, cursor, D1, nullptr);
@@ -351,15 +380,12 @@ __global__ __launch_bounds__(kThreads) void pack_wide_kernel(
         int32_t seq = -1;
         const int64_t pos = (int64_t)p + tid;
         if (tid < kWideRuns && pos < n_seq) {
-            const uint32_t i = (uint32_t)order[pos];
-            if (i < (uint32_t)n_seq) {
-                const int64_t g = (int64_t)block_of_seq[i] * T + offset_of_seq[i];
-                if (g < gs_hi) {
-                    lo = g * F;
-                    hi = lo + (int64_t)lengths[i] * F;
-                    from = src_offsets[i] * F;
-                    seq = (int32_t)i;
-                }
+            const Run r = runs[pos];
+            if (r.dst < gs_hi) {
+                lo = r.dst * F;
+                hi = lo + (int64_t)r.len * F;
+                from = r.src * F;
+                seq = r.seq;
             }
         }
         s_run_lo[tid] = lo;
@@ -557,6 +583,57 @@ __global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a,
     }
 }
 
+// ------------------------------------------------------------------ check
+//
+// Are the tables a plan: every rule is local to one shuffled position (or one block), so
+// one thread tests one of each; the smallest failing index is kept with an atomic minimum.
+__global__ __launch_bounds__(kThreads) void pack_check_kernel(
+    const int64_t* __restrict__ src_offsets, const int32_t* __restrict__ lengths,
+    const int32_t* __restrict__ order, const int32_t* __restrict__ block_of_seq,
+    const int32_t* __restrict__ offset_of_seq, const int32_t* __restrict__ block_first,
+    int32_t n_seq, int32_t num_blocks, int32_t t_blk, int64_t total_frames,
+    unsigned long long* __restrict__ first_bad)
+{
+    const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    bool bad = false;
+    // block idx: its range of positions
+    if (idx < num_blocks) {
+        const int64_t lo = block_first[idx], hi = block_first[idx + 1];
+        bad |= lo < 0 || hi < lo || hi > n_seq || (idx == 0 && lo != 0);
+    }
+    // position idx: its sequence
+    const int64_t listed = min(max((int64_t)block_first[num_blocks], (int64_t)0), (int64_t)n_seq);
+    if (idx < listed) {
+        const uint32_t i = (uint32_t)order[idx];
+        if (i >= (uint32_t)n_seq) {
+            bad = true;
+        } else {
+            const int64_t b = block_of_seq[i], off = offset_of_seq[i], len = lengths[i];
+            const int64_t from = src_offsets[i];
+            bad |= len < 1 || off < 0 || off + len > t_blk;
+            bad |= from < 0 || from + len > total_frames || src_offsets[i + 1] - from != len;
+            if (b < 0 || b >= num_blocks) {
+                bad = true;
+            } else {
+                const int64_t lo = block_first[b], hi = block_first[b + 1];
+                if (lo < 0 || idx < lo || idx >= hi) {
+                    bad = true;
+                } else if (idx == lo) {
+                    bad |= off != 0;
+                } else {
+                    const uint32_t before = (uint32_t)order[idx - 1];
+                    bad |= before >= (uint32_t)n_seq ||
+                           (before < (uint32_t)n_seq &&
+                            off != (int64_t)offset_of_seq[before] + (int64_t)lengths[before]);
+                }
+            }
+        }
+    }
+    if (bad) atomicMin(first_bad, (unsigned long long)idx);
+}
+
+__global__ void pack_check_clear_kernel(unsigned long long* first_bad) { *first_bad = ~0ull; }
+
 }  // namespace bload
 
 using namespace bload;
@@ -584,16 +661,121 @@ extern "C" int32_t bload_pack_tile_bytes(int64_t n_seq, int64_t num_blocks, int3
     return takes_wide_tiles(frame_bytes, total_slots * frame_bytes, n_seq, src_aligned_16 != 0) ? kWideTile : 0;
 }
 
-extern "C" size_t bload_pack_workspace_bytes(int64_t num_blocks, int32_t t_blk, int64_t frame_bytes)
+namespace {
+
+// Workspace: the run table, then one int32 per tile.
+struct PackLayout {
+    bool wide;
+    int64_t tiles;
+    size_t runs_off, first_off, bytes;
+};
+
+// Sizes the caller cannot know in advance (which tile shape the lengths will choose) are
+// taken at their larger value when `for_query`.
+bool pack_layout(int64_t n_seq, int64_t num_blocks, int32_t t_blk, int64_t frame_bytes,
+                 bool src_aligned16, bool for_query, PackLayout* l)
 {
-    if (num_blocks <= 0 || t_blk < 1 || frame_bytes < 1) return 0;
     const int64_t total_slots = num_blocks * (int64_t)t_blk;
-    if (total_slots >= ((int64_t)1 << 40) || total_slots > (((int64_t)1 << 52) - 1) / frame_bytes) return 0;
-    // one int32 per tile: 4 KiB of packed tensor or 1024 slots; frames that may take either
-    // shape (the choice depends on the lengths) get room for the 4 KiB tiles, which are more
-    const int64_t tiles = frame_bytes >= kWideMinFrame ? ceil_div(total_slots * frame_bytes, kWideTile)
-                                                       : ceil_div(total_slots, kNarrowSlots);
-    return round_up((size_t)tiles * sizeof(int32_t), 16);
+    if (total_slots >= ((int64_t)1 << 40) || total_slots > (((int64_t)1 << 52) - 1) / frame_bytes) return false;
+    const int64_t total_bytes = total_slots * frame_bytes;
+    const int64_t wide_tiles = ceil_div(total_bytes, kWideTile), narrow_tiles = ceil_div(total_slots, kNarrowSlots);
+    if (for_query) {
+        // frames that may take either shape get room for the 4 KiB tiles, which are more
+        l->wide = frame_bytes >= kWideMinFrame;
+        l->tiles = l->wide ? (wide_tiles > narrow_tiles ? wide_tiles : narrow_tiles) : narrow_tiles;
+    } else {
+        l->wide = takes_wide_tiles(frame_bytes, total_bytes, n_seq, src_aligned16);
+        l->tiles = l->wide ? wide_tiles : narrow_tiles;
+    }
+    l->runs_off = 0;
+    l->first_off = round_up((size_t)n_seq * sizeof(Run), 32);
+    l->bytes = l->first_off + round_up((size_t)l->tiles * sizeof(int32_t), 16);
+    return true;
+}
+
+// Argument checks shared by the entry points that pack.
+bload_status pack_check_args(const void* d_src, const int64_t* d_src_offsets, const int32_t* d_lengths,
+                             const int32_t* d_order, const int32_t* d_block_of_seq,
+                             const int32_t* d_offset_of_seq, const int32_t* d_block_first, int64_t n_seq,
+                             int64_t num_blocks, int32_t t_blk, int64_t frame_bytes, void* d_packed,
+                             int32_t* d_seq_id, int32_t* d_frame_idx, uint8_t* d_reset, uint8_t* d_valid)
+{
+    if (!d_src || !d_src_offsets || !d_lengths || !d_order || !d_block_of_seq ||
+        !d_offset_of_seq || !d_block_first || !d_packed || !d_seq_id || !d_frame_idx ||
+        !d_reset || !d_valid)
+        return BLOAD_EINVAL;
+    const int64_t total_slots = num_blocks * (int64_t)t_blk;
+    if (total_slots >= ((int64_t)1 << 40) || frame_bytes >= ((int64_t)1 << 31) ||
+        total_slots > INT64_MAX / frame_bytes / 2 || total_slots * frame_bytes >= ((int64_t)1 << 52))
+        return BLOAD_EOVERFLOW;
+    if (!aligned_to(d_packed, 16) || !aligned_to(d_seq_id, 16) || !aligned_to(d_frame_idx, 16) ||
+        !aligned_to(d_reset, 16) || !aligned_to(d_valid, 16) || !aligned_to(d_src_offsets, 8) ||
+        !aligned_to(d_lengths, 4) || !aligned_to(d_order, 4) || !aligned_to(d_block_of_seq, 4) ||
+        !aligned_to(d_offset_of_seq, 4) || !aligned_to(d_block_first, 4))
+        return BLOAD_EALIGN;
+    return BLOAD_OK;
+}
+
+// Enqueue the two passes.  `ws` holds l.bytes bytes, 32-byte aligned or better.
+bload_status pack_enqueue(const PackLayout& l, const void* d_src, const int64_t* d_src_offsets,
+                          const int32_t* d_lengths, const int32_t* d_order, const int32_t* d_block_of_seq,
+                          const int32_t* d_offset_of_seq, const int32_t* d_block_first, int64_t n_seq,
+                          int64_t num_blocks, int32_t t_blk, int64_t frame_bytes, void* d_packed,
+                          int32_t* d_seq_id, int32_t* d_frame_idx, uint8_t* d_reset, uint8_t* d_valid,
+                          uint8_t* ws, hipStream_t stream)
+{
+    if (l.tiles > INT32_MAX) return BLOAD_EOVERFLOW;
+    Run* runs = reinterpret_cast<Run*>(ws + l.runs_off);
+    int32_t* first_pos = reinterpret_cast<int32_t*>(ws + l.first_off);
+    PackArgs a;
+    a.src = static_cast<const uint8_t*>(d_src);
+    a.runs = runs;
+    a.n_seq = (int32_t)n_seq;
+    a.t_blk = t_blk;
+    a.frame_bytes = frame_bytes;
+    a.total_slots = num_blocks * (int64_t)t_blk;
+    a.packed = static_cast<uint8_t*>(d_packed);
+    a.seq_id = d_seq_id;
+    a.frame_idx = d_frame_idx;
+    a.reset = d_reset;
+    a.valid = d_valid;
+
+    // pass 1 (both tile shapes): the run table, and where each tile starts in it.  The
+    // narrow tiles are 1024 slots, which the kernel takes as "1024 bytes of 1-byte frames".
+    const int64_t unit_bytes = l.wide ? frame_bytes : 1;
+    const int32_t tile_units = l.wide ? kWideTile : kNarrowSlots;
+    const double inv_unit = 1.0 / (double)unit_bytes, inv_t = 1.0 / (double)t_blk;
+    const int64_t prepare_threads = l.tiles > n_seq ? l.tiles : n_seq;
+    hipLaunchKernelGGL(pack_prepare_kernel, dim3((uint32_t)ceil_div(prepare_threads, kThreads)),
+                       dim3(kThreads), 0, stream, d_src_offsets, d_lengths, d_order, d_block_of_seq,
+                       d_offset_of_seq, d_block_first, (int32_t)n_seq, num_blocks, (int64_t)t_blk, unit_bytes,
+                       l.tiles, tile_units, inv_unit, inv_t, runs, first_pos);
+    const dim3 grid((uint32_t)l.tiles), block(kThreads);
+    if (l.wide) {
+        hipLaunchKernelGGL(pack_wide_kernel, grid, block, 0, stream, a, runs, first_pos, kWideTile, inv_unit);
+    } else if (frame_bytes % 16 == 0 && aligned_to(d_src, 16)) {
+        hipLaunchKernelGGL((pack_narrow_kernel<vec16, false>), grid, block, 0, stream, a, first_pos);
+    } else if (frame_bytes == 4 && aligned_to(d_src, 4)) {
+        hipLaunchKernelGGL((pack_narrow_kernel<uint32_t, true>), grid, block, 0, stream, a, first_pos);
+    } else if (frame_bytes % 4 == 0 && aligned_to(d_src, 4)) {
+        hipLaunchKernelGGL((pack_narrow_kernel<uint32_t, false>), grid, block, 0, stream, a, first_pos);
+    } else if (frame_bytes % 2 == 0 && aligned_to(d_src, 2)) {
+        hipLaunchKernelGGL((pack_narrow_kernel<uint16_t, false>), grid, block, 0, stream, a, first_pos);
+    } else {
+        hipLaunchKernelGGL((pack_narrow_kernel<uint8_t, false>), grid, block, 0, stream, a, first_pos);
+    }
+    return launch_status();
+}
+
+}  // namespace
+
+extern "C" size_t bload_pack_workspace_bytes(int64_t n_seq, int64_t num_blocks, int32_t t_blk,
+                                             int64_t frame_bytes)
+{
+    if (n_seq <= 0 || n_seq > BLOAD_MAX_SEQ || num_blocks <= 0 || t_blk < 1 || frame_bytes < 1) return 0;
+    PackLayout l;
+    if (!pack_layout(n_seq, num_blocks, t_blk, frame_bytes, true, true, &l)) return 0;
+    return l.bytes;
 }
 
 extern "C" bload_status bload_pack(const void* d_src, const int64_t* d_src_offsets,
@@ -609,70 +791,54 @@ extern "C" bload_status bload_pack(const void* d_src, const int64_t* d_src_offse
     if (n_seq > BLOAD_MAX_SEQ || num_blocks > n_seq) return n_seq > BLOAD_MAX_SEQ ? BLOAD_EOVERFLOW
                                                                                  : BLOAD_EINVAL;
     if (n_seq == 0 || num_blocks == 0) return BLOAD_OK;
-    if (!d_src || !d_src_offsets || !d_lengths || !d_order || !d_block_of_seq ||
-        !d_offset_of_seq || !d_block_first || !d_packed || !d_seq_id || !d_frame_idx ||
-        !d_reset || !d_valid)
-        return BLOAD_EINVAL;
-    const int64_t total_slots = num_blocks * (int64_t)t_blk;
-    if (total_slots >= ((int64_t)1 << 40) || frame_bytes >= ((int64_t)1 << 31) ||
-        total_slots > INT64_MAX / frame_bytes / 2)
+    const bload_status st = pack_check_args(d_src, d_src_offsets, d_lengths, d_order, d_block_of_seq,
+                                            d_offset_of_seq, d_block_first, n_seq, num_blocks, t_blk,
+                                            frame_bytes, d_packed, d_seq_id, d_frame_idx, d_reset, d_valid);
+    if (st != BLOAD_OK) return st;
+    PackLayout l;
+    if (!pack_layout(n_seq, num_blocks, t_blk, frame_bytes, aligned_to(d_src, 16), false, &l))
         return BLOAD_EOVERFLOW;
-    if (!aligned_to(d_packed, 16) || !aligned_to(d_seq_id, 16) || !aligned_to(d_frame_idx, 16) ||
-        !aligned_to(d_reset, 16) || !aligned_to(d_valid, 16) || !aligned_to(d_src_offsets, 8) ||
-        !aligned_to(d_lengths, 4) || !aligned_to(d_order, 4) || !aligned_to(d_block_of_seq, 4) ||
-        !aligned_to(d_offset_of_seq, 4) || !aligned_to(d_block_first, 4))
-        return BLOAD_EALIGN;
-
-    PackArgs a;
-    a.src = static_cast<const uint8_t*>(d_src);
-    a.src_offsets = d_src_offsets;
-    a.lengths = d_lengths;
-    a.order = d_order;
-    a.block_of_seq = d_block_of_seq;
-    a.offset_of_seq = d_offset_of_seq;
-    a.block_first = d_block_first;
-    a.n_seq = (int32_t)n_seq;
-    a.t_blk = t_blk;
-    a.frame_bytes = frame_bytes;
-    a.total_slots = total_slots;
-    a.packed = static_cast<uint8_t*>(d_packed);
-    a.seq_id = d_seq_id;
-    a.frame_idx = d_frame_idx;
-    a.reset = d_reset;
-    a.valid = d_valid;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-
-    // pass 1 (both tile shapes): where each tile starts in the shuffled order.  The
-    // narrow tiles are 1024 slots, which the kernel takes as "1024 bytes of 1-byte frames".
-    const int64_t total_bytes = total_slots * frame_bytes;
-    if (total_bytes >= ((int64_t)1 << 52)) return BLOAD_EOVERFLOW;
-    const bool wide = takes_wide_tiles(frame_bytes, total_bytes, n_seq, aligned_to(d_src, 16));
-    const int64_t tiles = wide ? ceil_div(total_bytes, kWideTile) : ceil_div(total_slots, kNarrowSlots);
-    if (tiles > INT32_MAX) return BLOAD_EOVERFLOW;
     if (!d_workspace) return BLOAD_EINVAL;
-    if (!aligned_to(d_workspace, 16)) return BLOAD_EALIGN;
-    if (workspace_bytes < (size_t)tiles * sizeof(int32_t)) return BLOAD_EWORKSPACE;
-    int32_t* first_pos = static_cast<int32_t*>(d_workspace);
-    const int64_t unit_bytes = wide ? frame_bytes : 1;
-    const int32_t tile_units = wide ? kWideTile : kNarrowSlots;
-    const double inv_unit = 1.0 / (double)unit_bytes, inv_t = 1.0 / (double)t_blk;
-    hipLaunchKernelGGL(pack_locate_kernel, dim3((uint32_t)ceil_div(tiles, kThreads)), dim3(kThreads), 0,
-                       stream, d_order, d_offset_of_seq, d_block_first, (int32_t)n_seq, (int64_t)t_blk,
-                       unit_bytes, tiles, tile_units, inv_unit, inv_t, first_pos);
-    const dim3 grid((uint32_t)tiles), block(kThreads);
-    if (wide) {
-        hipLaunchKernelGGL(pack_wide_kernel, grid, block, 0, stream, a, d_src_offsets, d_lengths,
-                           d_order, d_block_of_seq, d_offset_of_seq, first_pos, kWideTile, inv_unit);
-    } else if (frame_bytes % 16 == 0 && aligned_to(d_src, 16)) {
-        hipLaunchKernelGGL((pack_narrow_kernel<vec16, false>), grid, block, 0, stream, a, first_pos);
-    } else if (frame_bytes == 4 && aligned_to(d_src, 4)) {
-        hipLaunchKernelGGL((pack_narrow_kernel<uint32_t, true>), grid, block, 0, stream, a, first_pos);
-    } else if (frame_bytes % 4 == 0 && aligned_to(d_src, 4)) {
-        hipLaunchKernelGGL((pack_narrow_kernel<uint32_t, false>), grid, block, 0, stream, a, first_pos);
-    } else if (frame_bytes % 2 == 0 && aligned_to(d_src, 2)) {
-        hipLaunchKernelGGL((pack_narrow_kernel<uint16_t, false>), grid, block, 0, stream, a, first_pos);
-    } else {
-        hipLaunchKernelGGL((pack_narrow_kernel<uint8_t, false>), grid, block, 0, stream, a, first_pos);
-    }
-    return launch_status();
+    if (!aligned_to(d_workspace, 32)) return BLOAD_EALIGN;
+    if (workspace_bytes < l.bytes) return BLOAD_EWORKSPACE;
+    return pack_enqueue(l, d_src, d_src_offsets, d_lengths, d_order, d_block_of_seq, d_offset_of_seq,
+                        d_block_first, n_seq, num_blocks, t_blk, frame_bytes, d_packed, d_seq_id,
+                        d_frame_idx, d_reset, d_valid, static_cast<uint8_t*>(d_workspace),
+                        static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" bload_status bload_pack_check(const int64_t* d_src_offsets, const int32_t* d_lengths,
+                                         const int32_t* d_order, const int32_t* d_block_of_seq,
+                                         const int32_t* d_offset_of_seq, const int32_t* d_block_first,
+                                         int64_t n_seq, int64_t num_blocks, int32_t t_blk,
+                                         int64_t total_frames, int64_t* h_first_bad, void* d_workspace,
+                                         size_t workspace_bytes, void* hip_stream)
+{
+    if (h_first_bad) *h_first_bad = -1;
+    if (n_seq < 0 || num_blocks < 0 || t_blk < 1 || total_frames < 0) return BLOAD_EINVAL;
+    if (n_seq > BLOAD_MAX_SEQ) return BLOAD_EOVERFLOW;
+    if (num_blocks > n_seq) return BLOAD_EINVAL;
+    if (n_seq == 0 || num_blocks == 0) return BLOAD_OK;
+    if (!d_src_offsets || !d_lengths || !d_order || !d_block_of_seq || !d_offset_of_seq ||
+        !d_block_first || !d_workspace)
+        return BLOAD_EINVAL;
+    if (!aligned_to(d_src_offsets, 8) || !aligned_to(d_lengths, 4) || !aligned_to(d_order, 4) ||
+        !aligned_to(d_block_of_seq, 4) || !aligned_to(d_offset_of_seq, 4) ||
+        !aligned_to(d_block_first, 4) || !aligned_to(d_workspace, 16))
+        return BLOAD_EALIGN;
+    if (workspace_bytes < 16) return BLOAD_EWORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    unsigned long long* first_bad = static_cast<unsigned long long*>(d_workspace);
+    hipLaunchKernelGGL(pack_check_clear_kernel, dim3(1), dim3(1), 0, stream, first_bad);
+    hipLaunchKernelGGL(pack_check_kernel, dim3((uint32_t)ceil_div(n_seq, kThreads)), dim3(kThreads), 0,
+                       stream, d_src_offsets, d_lengths, d_order, d_block_of_seq, d_offset_of_seq,
+                       d_block_first, (int32_t)n_seq, (int32_t)num_blocks, t_blk, total_frames, first_bad);
+    if (launch_status() != BLOAD_OK) return BLOAD_EHIP;
+    unsigned long long host = 0;
+    if (!hip_ok(hipMemcpyAsync(&host, first_bad, sizeof(host), hipMemcpyDeviceToHost, stream)))
+        return BLOAD_EHIP;
+    if (!hip_ok(hipStreamSynchronize(stream))) return BLOAD_EHIP;
+    if (host == ~0ull) return BLOAD_OK;
+    if (h_first_bad) *h_first_bad = (int64_t)host;
+    return BLOAD_EINVAL;
 }

@@ -25,6 +25,10 @@ int64_t bload_oracle_plan_shard(const int32_t* order, const int32_t* block_of_se
                                 const int32_t* block_first, int64_t n, int64_t num_blocks,
                                 int32_t rank, int32_t world, int32_t* order_local,
                                 int32_t* block_of_seq_local, int32_t* block_first_local);
+int64_t bload_oracle_plan_check(const int64_t* src_offsets, const int32_t* lengths, const int32_t* order,
+                                const int32_t* block_of_seq, const int32_t* offset_of_seq,
+                                const int32_t* block_first, int64_t n, int64_t num_blocks, int32_t t_blk,
+                                int64_t total_frames);
 
 int main(void)
 {
@@ -45,6 +49,11 @@ int main(void)
     bload_oracle_order(N, 12345, order);
     if (bload_oracle_plan(lengths, N, T, order, block_of, offset_of, block_first, &B, &frames) != 0) return 2;
     if (frames != total || B < 1 || block_first[B] != N) return 3;
+    so[N] = total;
+    if (bload_oracle_plan_check(so, lengths, order, block_of, offset_of, block_first, N, B, T, total) != -1) return 10;
+    offset_of[order[40]] += 1;
+    if (bload_oracle_plan_check(so, lengths, order, block_of, offset_of, block_first, N, B, T, total) != 40) return 11;
+    offset_of[order[40]] -= 1;
 
     size_t slots = (size_t)B * T;
     uint8_t* packed = malloc(slots * D * 4);

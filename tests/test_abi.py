@@ -106,6 +106,7 @@ def test_argument_checks_need_no_gpu(lib):
     assert 28 * 10**6 <= w(10**6) <= 28 * 10**6 + 70000
     lib.bload_pack.restype = ctypes.c_int
     lib.bload_pack.argtypes = [vp] * 7 + [i64, i64, i32, i64] + [vp] * 6 + [ctypes.c_size_t, vp]
+    p = 0x1000 * 2                                  # 32-byte aligned, never dereferenced
     ok = [p] * 7 + [4, 2, 8, 16] + [p] * 5 + [p, 1 << 20, None]
     assert lib.bload_pack(*(ok[:7] + [4, 2, 0, 16] + ok[11:])) == 1          # t_blk < 1
     assert lib.bload_pack(*(ok[:7] + [4, 2, 8, 0] + ok[11:])) == 1           # frame_bytes < 1
@@ -115,10 +116,22 @@ def test_argument_checks_need_no_gpu(lib):
     assert lib.bload_pack(*(ok[:7] + [4, 2, 8, 4096] + ok[11:16] + [p, 8, None])) == 3   # workspace
     f = lib.bload_pack_workspace_bytes
     f.restype = ctypes.c_size_t
-    f.argtypes = [i64, i32, i64]
-    need = 4 * -(-180 * 600 * 37632 // 4096)         # one int32 per 4 KiB tile
-    assert need <= f(180, 600, 37632) < need + 16 and f(180, 600, 37632) % 16 == 0
-    assert f(180, 600, 4) == 4 * -(-180 * 600 // 1024) + 8 and f(0, 600, 4096) == 0
+    f.argtypes = [i64, i64, i32, i64]
+    need = 32 * 1000 + 4 * -(-180 * 600 * 37632 // 4096)     # a 32-byte run per sequence, an int32 per 4 KiB tile
+    assert need <= f(1000, 180, 600, 37632) < need + 16 and f(1000, 180, 600, 37632) % 16 == 0
+    assert f(1000, 180, 600, 4) == 32 * 1000 + 4 * -(-180 * 600 // 1024) + 8
+    assert f(1000, 0, 600, 4096) == 0 and f(0, 5, 600, 4096) == 0
+    assert f(10**6, 200, 8, 64) >= 32 * 10**6 + 4 * 2          # frames that may take either tile shape
+    chk = lib.bload_pack_check
+    chk.restype = ctypes.c_int
+    chk.argtypes = [vp] * 6 + [i64, i64, i32, i64, ctypes.POINTER(i64), vp, ctypes.c_size_t, vp]
+    bad = i64(7)
+    assert chk(p, p, p, p, p, p, 4, 2, 0, 9, bad, p, 16, None) == 1 and bad.value == -1     # t_blk < 1
+    assert chk(p, p, p, p, p, p, 4, 5, 8, 9, bad, p, 16, None) == 1                        # more blocks than sequences
+    assert chk(None, p, p, p, p, p, 4, 2, 8, 9, bad, p, 16, None) == 1
+    assert chk(p, p, p, p, p, p, 4, 2, 8, 9, None, p, 8, None) == 3
+    assert chk(p, p, p + 2, p, p, p, 4, 2, 8, 9, bad, p, 16, None) == 4
+    assert chk(p, p, p, p, p, p, 0, 0, 8, 0, bad, p, 16, None) == 0
     tb = lib.bload_pack_tile_bytes
     tb.restype = i32
     tb.argtypes = [i64, i64, i32, i64, i32]

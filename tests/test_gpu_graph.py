@@ -31,7 +31,7 @@ def test_captured_pack_reduce_scan_replays_like_eager(F, dtype):
 
     src = draw()
     packed = bl.alloc_packed(B, T, F, src.device)
-    pack_ws = torch.empty(max(16, bl.bload_pack_workspace_bytes(B, T, F)), dtype=torch.uint8, device="cuda")
+    pack_ws = torch.empty(max(32, bl.bload_pack_workspace_bytes(n, B, T, F)), dtype=torch.uint8, device="cuda")
     red_ws = torch.empty(max(16, bl.bload_segment_reduce_workspace_bytes(B, T, D, dtype)), dtype=torch.uint8,
                          device="cuda")
     scan_ws = torch.empty(max(16, bl.bload_segment_scan_workspace_bytes(B, T, D, dtype)), dtype=torch.uint8,
