@@ -19,11 +19,14 @@
  *   bload_segment_scan      a recurrent consumer that drops its state at sequence starts
  *   bload_strategy_counts   padding / frames deleted under the strategies the paper compares
  *   bload_pack_check        are these tables a plan bload_pack can take
+ *   bload_pack_noalloc      bload_pack with its scratch in a fixed array of the library
  *
  * Conventions
  *   - Pointers named d_* are DEVICE pointers (hipMalloc-style memory of the
  *     current device), h_* are HOST pointers.  The caller owns every buffer;
- *     the library allocates nothing and keeps no state between calls.
+ *     the library allocates nothing and keeps no state between calls (the one
+ *     exception, a fixed scratch array, is bload_pack_noalloc's and is described
+ *     there).
  *   - A frame is an opaque record of `frame_bytes` bytes (H*W*C*sizeof(elem));
  *     H and W are the same for all sequences of one call.
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the null stream).
@@ -227,6 +230,32 @@ bload_status bload_pack(const void* d_src, const int64_t* d_src_offsets, const i
                         void* d_packed, int32_t* d_seq_id, int32_t* d_frame_idx,
                         uint8_t* d_reset, uint8_t* d_valid,
                         void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): bload_pack without the
+ * workspace argument.  Its scratch -- the same per-sequence records and per-tile
+ * entries -- lives in a fixed array of 16 MiB of device memory that belongs to the
+ * loaded library; every GPU on which this entry point is used holds one until the
+ * process ends.  Limits: n_seq <= BLOAD_PACK_NOALLOC_MAX_SEQ and at most
+ * BLOAD_PACK_NOALLOC_MAX_TILES destination tiles (a tile is 4 KiB of packed tensor
+ * when bload_pack_tile_bytes() says 4096, else 1024 slots: 8 GiB of packed tensor,
+ * or 2^31 slots); anything larger is refused with BLOAD_EOVERFLOW before anything
+ * is launched.  All other arguments, checks and results are those of bload_pack.
+ * The call allocates and frees nothing and does not synchronise.  Nothing in the
+ * array has to be cleared between calls (each call rewrites the part it reads),
+ * but all calls on one GPU share it: two such calls must not overlap in time on
+ * the same GPU (calls on one stream never do; calls on different streams, or from
+ * different threads, need an order between them).
+ */
+#define BLOAD_PACK_NOALLOC_MAX_SEQ ((int64_t)1 << 18)
+#define BLOAD_PACK_NOALLOC_MAX_TILES ((int64_t)1 << 21)
+
+bload_status bload_pack_noalloc(const void* d_src, const int64_t* d_src_offsets, const int32_t* d_lengths,
+                                const int32_t* d_order, const int32_t* d_block_of_seq,
+                                const int32_t* d_offset_of_seq, const int32_t* d_block_first,
+                                int64_t n_seq, int64_t num_blocks, int32_t t_blk, int64_t frame_bytes,
+                                void* d_packed, int32_t* d_seq_id, int32_t* d_frame_idx,
+                                uint8_t* d_reset, uint8_t* d_valid, void* hip_stream);
 
 /* Methods section: whole sequences, one after another from the block's first
  * slot, none split, none beyond the block's end.  This call verifies that the

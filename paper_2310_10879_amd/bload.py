@@ -56,6 +56,9 @@ _lib.bload_pack_tile_bytes.argtypes = [_i64, _i64, _i32, _i64, _i32]
 _lib.bload_pack.restype = ctypes.c_int
 _lib.bload_pack.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i32, _i64,
                             _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.bload_pack_noalloc.restype = ctypes.c_int
+_lib.bload_pack_noalloc.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i32, _i64,
+                                    _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.bload_pack_check.restype = ctypes.c_int
 _lib.bload_pack_check.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i32, _i64,
                                   ctypes.POINTER(_i64), _vp, _sz, _vp]
@@ -267,6 +270,31 @@ def bload_pack(src: torch.Tensor, src_offsets: torch.Tensor, lengths: torch.Tens
                          _ptr(out.frame_idx, torch.int32), _ptr(out.reset, torch.uint8),
                          _ptr(out.valid, torch.uint8), _ptr(workspace),
                          workspace.numel() * workspace.element_size(), _stream())
+    _check(st)
+    return out
+
+
+PACK_NOALLOC_MAX_SEQ = 1 << 18
+PACK_NOALLOC_MAX_TILES = 1 << 21
+
+
+def bload_pack_noalloc(src: torch.Tensor, src_offsets: torch.Tensor, lengths: torch.Tensor, plan: Plan,
+                       frame_bytes: int, out: Packed) -> Packed:
+    """``bload_pack`` with its scratch in the library's fixed device array: nothing is allocated
+    here or in the library, so ``out`` must be brought along.  Asynchronous on the current
+    stream; calls on one GPU must not overlap."""
+    if src.numel() * src.element_size() != plan.total_frames * frame_bytes:
+        raise ValueError("source size does not match total_frames * frame_bytes")
+    if out.packed.numel() != plan.num_blocks * plan.t_blk * frame_bytes or \
+            out.seq_id.numel() != plan.num_blocks * plan.t_blk:
+        raise ValueError("output buffers do not match num_blocks * t_blk")
+    st = _lib.bload_pack_noalloc(_ptr(src), _ptr(src_offsets, torch.int64), _ptr(lengths, torch.int32),
+                                 _ptr(plan.order, torch.int32), _ptr(plan.block_of_seq, torch.int32),
+                                 _ptr(plan.offset_of_seq, torch.int32), _ptr(plan.block_first, torch.int32),
+                                 lengths.shape[0], plan.num_blocks, plan.t_blk, frame_bytes,
+                                 _ptr(out.packed, torch.uint8), _ptr(out.seq_id, torch.int32),
+                                 _ptr(out.frame_idx, torch.int32), _ptr(out.reset, torch.uint8),
+                                 _ptr(out.valid, torch.uint8), _stream())
     _check(st)
     return out
 

@@ -26,6 +26,8 @@
 
 #include <limits.h>
 
+#include <mutex>
+
 namespace bload {
 
 // Where one sequence goes: the record the copy kernels work from.  Position p of the
@@ -805,6 +807,71 @@ extern "C" bload_status bload_pack(const void* d_src, const int64_t* d_src_offse
                         d_block_first, n_seq, num_blocks, t_blk, frame_bytes, d_packed, d_seq_id,
                         d_frame_idx, d_reset, d_valid, static_cast<uint8_t*>(d_workspace),
                         static_cast<hipStream_t>(hip_stream));
+}
+
+// ---------------------------------------------------- bload_pack_noalloc
+//
+// bload_pack for callers that cannot bring a workspace: the run table and the tiles'
+// entries live in a fixed array in device memory that is part of the loaded library.
+// Every GPU the library runs on holds its own copy of the array, at its own address,
+// until the process ends; the address is asked for once per device.
+
+constexpr size_t kStaticRunBytes = (size_t)BLOAD_PACK_NOALLOC_MAX_SEQ * sizeof(Run);
+constexpr size_t kStaticBytes = kStaticRunBytes + (size_t)BLOAD_PACK_NOALLOC_MAX_TILES * sizeof(int32_t);
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_of_device[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device.
+bload_status static_scratch(uint8_t** out)
+{
+    int dev = -1;
+    if (!hip_ok(hipGetDevice(&dev))) return BLOAD_EHIP;
+    if (dev < 0 || dev >= kMaxDevices) return BLOAD_EINVAL;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_of_device[dev]) {
+        void* ptr = nullptr;
+        if (!hip_ok(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch))) || !ptr) return BLOAD_EHIP;
+        g_scratch_of_device[dev] = ptr;
+    }
+    *out = static_cast<uint8_t*>(g_scratch_of_device[dev]);
+    return BLOAD_OK;
+}
+
+}  // namespace
+
+extern "C" bload_status bload_pack_noalloc(const void* d_src, const int64_t* d_src_offsets,
+                                           const int32_t* d_lengths, const int32_t* d_order,
+                                           const int32_t* d_block_of_seq, const int32_t* d_offset_of_seq,
+                                           const int32_t* d_block_first, int64_t n_seq,
+                                           int64_t num_blocks, int32_t t_blk, int64_t frame_bytes,
+                                           void* d_packed, int32_t* d_seq_id, int32_t* d_frame_idx,
+                                           uint8_t* d_reset, uint8_t* d_valid, void* hip_stream)
+{
+    if (n_seq < 0 || num_blocks < 0 || t_blk < 1 || frame_bytes < 1) return BLOAD_EINVAL;
+    if (n_seq > BLOAD_MAX_SEQ || num_blocks > n_seq) return n_seq > BLOAD_MAX_SEQ ? BLOAD_EOVERFLOW
+                                                                                 : BLOAD_EINVAL;
+    if (n_seq == 0 || num_blocks == 0) return BLOAD_OK;
+    const bload_status st = pack_check_args(d_src, d_src_offsets, d_lengths, d_order, d_block_of_seq,
+                                            d_offset_of_seq, d_block_first, n_seq, num_blocks, t_blk,
+                                            frame_bytes, d_packed, d_seq_id, d_frame_idx, d_reset, d_valid);
+    if (st != BLOAD_OK) return st;
+    PackLayout l;
+    if (!pack_layout(n_seq, num_blocks, t_blk, frame_bytes, aligned_to(d_src, 16), false, &l))
+        return BLOAD_EOVERFLOW;
+    // the fixed array holds this many runs and tiles, no more
+    if (n_seq > BLOAD_PACK_NOALLOC_MAX_SEQ || l.tiles > BLOAD_PACK_NOALLOC_MAX_TILES) return BLOAD_EOVERFLOW;
+    l.first_off = kStaticRunBytes;
+    uint8_t* ws = nullptr;
+    const bload_status got = static_scratch(&ws);
+    if (got != BLOAD_OK) return got;
+    return pack_enqueue(l, d_src, d_src_offsets, d_lengths, d_order, d_block_of_seq, d_offset_of_seq,
+                        d_block_first, n_seq, num_blocks, t_blk, frame_bytes, d_packed, d_seq_id,
+                        d_frame_idx, d_reset, d_valid, ws, static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" bload_status bload_pack_check(const int64_t* d_src_offsets, const int32_t* d_lengths,
