@@ -19,7 +19,7 @@
 //          row of lanes (at most one wave) walks one chunk of time serially
 //          with several loads in flight, restarting its accumulators at every
 //          start flag.
-//   narrow (small frames, e.g. one token): lanes across time, 8 consecutive
+//   narrow (small frames, e.g. one token): lanes across time, 16 consecutive
 //          slots per lane, segmented scan over the workgroup with the segment
 //          breaks as heads and a carry between lanes and waves.
 #include "bload_common.hpp"
@@ -387,68 +387,84 @@ __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
 
 // ----------------------------------------------------------------- narrow
 //
-// Lanes across time: a workgroup takes 2048 consecutive slots (a "tile", which
-// may span several blocks), a lane 8 consecutive slots.  From the flags every
-// lane builds two 8-bit masks: valid, and "break" (a slot that cannot continue
+// Lanes across time: a workgroup takes 4096 consecutive slots (a "tile", which
+// may span several blocks), a lane 16 consecutive slots.  From the flags every
+// lane builds two 16-bit masks: valid, and "break" (a slot that cannot continue
 // the segment of the slot before it: padding, a start flag, a block's first
 // slot, or a slot that follows padding).  Sums are a segmented scan with the
-// breaks as heads: inside the lane, across the wave with shuffles, across the
-// four waves through LDS.  Frame counts need no scan: a segment's frames are
-// consecutive, so its count is (end position - position of its break + 1).
+// breaks as heads: a lane contributes the sum of its slots from its last break
+// on (all its slots if it has none); the scan runs across the wave without LDS
+// (DPP) and across the four waves through LDS, and gives every lane the sum of
+// the segment that is open in front of it.  Only a lane in which a segment ends
+// -- rare when segments are long -- then walks its 16 slots.  Frame counts need
+// no scan: a segment's frames are consecutive, so its count is (end position -
+// position of its break + 1).  Integer sums are exact, float sums add only the
+// segment's own terms (no cancellation against neighbouring segments).
 
-constexpr int kSlotsPerLane = 8;
-constexpr int kNarrowTile = kThreads * kSlotsPerLane;      // 2048 slots per workgroup
+constexpr int kSlotsPerLane = 16;
+constexpr int kNarrowTile = kThreads * kSlotsPerLane;      // 4096 slots per workgroup
 
 // Running state of a segmented sum: `any` = a break was seen.
 template <typename Acc>
-struct SegState { Acc sum; int32_t any; };
+struct SegState { Acc sum; uint32_t any; };
 
 template <typename Acc>
-__device__ __forceinline__ SegState<Acc> seg_combine(SegState<Acc> left, SegState<Acc> right)
-{
-    SegState<Acc> r;
-    r.sum = right.any ? right.sum : left.sum + right.sum;
-    r.any = left.any | right.any;
-    return r;
-}
-
-__device__ __forceinline__ float shfl_up_acc(float v, int d) { return __shfl_up(v, d, kWave); }
-__device__ __forceinline__ long long shfl_up_acc(long long v, int d) { return __shfl_up(v, d, kWave); }
+struct SegCombine {
+    __device__ __forceinline__ SegState<Acc> operator()(SegState<Acc> left, SegState<Acc> right) const
+    {
+        SegState<Acc> r;
+        r.sum = right.any ? right.sum : left.sum + right.sum;
+        r.any = left.any | right.any;
+        return r;
+    }
+};
 
 template <typename Acc>
-__device__ __forceinline__ SegState<Acc> seg_shfl_up(SegState<Acc> s, int d)
+struct SegMove {
+    template <int CTRL, int ROW_MASK>
+    __device__ __forceinline__ SegState<Acc> at(SegState<Acc> s) const
+    {
+        return SegState<Acc>{dpp_move<CTRL, ROW_MASK>(s.sum, (Acc)0), dpp_move<CTRL, ROW_MASK>(s.any, 0u)};
+    }
+};
+
+// Bit j of the result: byte j of the 16 flag bytes is non-zero.
+__device__ __forceinline__ uint32_t nonzero_bytes16(vec16 w)
 {
-    SegState<Acc> r;
-    r.sum = shfl_up_acc(s.sum, d);
-    r.any = __shfl_up(s.any, d, kWave);
-    return r;
+    uint32_t m = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t x = w[k];
+        // top bit of every non-zero byte, then bits 7, 15, 23, 31 -> bits 0 .. 3
+        const uint32_t t = ((((x & 0x7f7f7f7fu) + 0x7f7f7f7fu) | x) & 0x80808080u) >> 7;
+        m |= ((t | (t >> 7) | (t >> 14) | (t >> 21)) & 0xFu) << (4 * k);
+    }
+    return m;
 }
 
-// What a lane knows about its 8 slots after reading the flags.
-struct LaneSegments {
+// What a lane knows about its 16 slots after reading the flags.
+struct LaneFlags {
     uint32_t vmask;        // bit j: slot j is valid
     uint32_t bmask;        // bit j: slot j is a break
     uint32_t ends;         // bit j: a segment ends at slot j
-    int32_t prev_start;    // tile-relative position of the last break before this lane, -1 if none
-    int32_t j_last;        // index of the tile's last slot in this lane (may lie outside 0..7)
+    int32_t j_last;        // index of the tile's last slot in this lane (may lie outside 0..15)
     bool tail_open;        // the tile's last slot is here and its segment goes on into the next tile
 };
 
-// Reads the flags of the lane's slots and of its neighbours and derives the
-// masks.  Called by every thread of the workgroup; contains one barrier.
-// s_wave_start: LDS scratch, one int per wave.
-__device__ __forceinline__ LaneSegments narrow_lane_segments(const ReduceArgs& a, int64_t g0, int64_t g1,
-                                                             int32_t* s_wave_start)
+// Reads the flags of the lane's slots and of its neighbours and derives the masks.  Called by
+// every thread of the workgroup (the lanes of a wave exchange their border slots).
+__device__ __forceinline__ LaneFlags narrow_lane_flags(const ReduceArgs& a, int64_t g0, int64_t g1)
 {
     constexpr int SPL = kSlotsPerLane;
+    constexpr uint32_t ALL = (1u << SPL) - 1u;
     const int tid = (int)threadIdx.x;
-    const int lane = lane_id(), wave = wave_id();
+    const int lane = lane_id();
     const int64_t S = a.total_slots;
     const uint32_t T = (uint32_t)a.t_blk;
     const int pos0 = tid * SPL;
     const int64_t s0 = g0 + pos0;
     const int64_t sn = s0 + SPL;                         // the slot after this lane's last one
-    LaneSegments r;
+    LaneFlags r;
 
     uint8_t before_valid = 0, after_valid = 0, after_reset = 0;
     if (lane == 0 && s0 > 0 && s0 <= S) before_valid = a.valid[s0 - 1];
@@ -456,15 +472,11 @@ __device__ __forceinline__ LaneSegments narrow_lane_segments(const ReduceArgs& a
 
     uint32_t vmask = 0, rmask = 0;
     if (sn <= S) {
-        typedef uint32_t flag_words __attribute__((ext_vector_type(SPL / 4)));
-        union { flag_words v; uint8_t b[SPL]; } ur, uv;
-        ur.v = __builtin_nontemporal_load(reinterpret_cast<const flag_words*>(a.reset + s0));
-        uv.v = __builtin_nontemporal_load(reinterpret_cast<const flag_words*>(a.valid + s0));
-#pragma unroll
-        for (int j = 0; j < SPL; ++j) {
-            vmask |= (uint32_t)(uv.b[j] != 0) << j;
-            rmask |= (uint32_t)(ur.b[j] != 0) << j;
-        }
+        static_assert(SPL == 16, "the flags of a lane are one 16-byte vector per plane");
+        const vec16 uv = load_stream(reinterpret_cast<const vec16*>(a.valid + s0));
+        const vec16 ur = load_stream(reinterpret_cast<const vec16*>(a.reset + s0));
+        vmask = nonzero_bytes16(uv);
+        rmask = nonzero_bytes16(ur);
     } else {
 #pragma unroll
         for (int j = 0; j < SPL; ++j) {
@@ -491,12 +503,12 @@ __device__ __forceinline__ LaneSegments narrow_lane_segments(const ReduceArgs& a
         if (rem_next >= T) rem_next %= T;
     }
     // validity of the slot before this lane's first one
-    uint32_t prev_valid = __shfl_up((vmask >> (SPL - 1)) & 1u, 1, kWave);
+    uint32_t prev_valid = dpp_move<kDppWaveShr1>((vmask >> (SPL - 1)) & 1u, 0u);
     if (lane == 0) prev_valid = (uint32_t)(before_valid != 0);
     const uint32_t after_pad = ~((vmask << 1) | prev_valid);          // bit j: slot j-1 is not valid
-    const uint32_t bmask = (~vmask | rmask | smask | after_pad) & ((1u << SPL) - 1u);
+    const uint32_t bmask = (~vmask | rmask | smask | after_pad) & ALL;
     // is the slot after this lane's last one a break
-    uint32_t next_first = __shfl_down(bmask & 1u, 1, kWave);
+    uint32_t next_first = dpp_move<kDppWaveShl1>(bmask & 1u, 0u);
     if (lane == kWave - 1) {
         next_first = 1u;
         if (sn < S && rem_next != 0)
@@ -509,69 +521,36 @@ __device__ __forceinline__ LaneSegments narrow_lane_segments(const ReduceArgs& a
     r.j_last = (int32_t)(g1 - 1 - s0);
     r.tail_open = r.j_last >= 0 && r.j_last < SPL && ((vmask >> r.j_last) & 1u) &&
                   !((next_brk >> r.j_last) & 1u);
-
-    // position of the last break before this lane: inside the wave by a vote,
-    // from the waves before through LDS
-    const int32_t own_last = bmask ? pos0 + (31 - __clz((int)bmask)) : -1;
-    const uint64_t any_lanes = __ballot(bmask != 0);
-    const uint64_t lower = any_lanes & ((1ull << lane) - 1ull);
-    const int32_t got = __shfl(own_last, lower ? 63 - __clzll((long long)lower) : 0, kWave);
-    r.prev_start = lower ? got : -1;
-    const int32_t wave_last = __shfl(own_last, any_lanes ? 63 - __clzll((long long)any_lanes) : 0, kWave);
-    if (lane == 0) s_wave_start[wave] = any_lanes ? wave_last : -1;
-    __syncthreads();
-    if (r.prev_start < 0) {
-        for (int w = wave - 1; w >= 0; --w) {
-            const int32_t st = s_wave_start[w];
-            if (st >= 0) { r.prev_start = st; break; }
-        }
-    }
     return r;
 }
 
-// Single-feature frames of 4-byte elements: the lane's 8 elements are 32
-// contiguous bytes whose address does not depend on the flags, so they can be
-// requested before the flags are looked at.
-struct NarrowEarly { vec16 raw[kSlotsPerLane / 4]; bool used; };
-
-template <typename ElemT>
-__device__ __forceinline__ NarrowEarly narrow_load_early(const ReduceArgs& a, int64_t s0)
-{
-    NarrowEarly e;
-    e.used = a.feat_dim == 1 && sizeof(ElemT) == 4 && s0 + kSlotsPerLane <= a.total_slots;
-    if (e.used) {
-#pragma unroll
-        for (int k = 0; k < kSlotsPerLane / 4; ++k)
-            e.raw[k] = load_stream(reinterpret_cast<const vec16*>(a.packed + (s0 + 4 * k) * (int64_t)sizeof(ElemT)));
-    }
-    return e;
-}
-
-// The lane's elements of feature d, 0 where the slot is not valid.
-template <typename ElemT, typename Acc>
-__device__ __forceinline__ void narrow_load(const ReduceArgs& a, int64_t s0, int d, uint32_t vmask,
-                                            const NarrowEarly& early, Acc (&x)[kSlotsPerLane])
+// The lane's 16 elements of feature d (whatever lies there; the caller masks them).  ONE: a
+// frame is one element, so they are contiguous and come as 16-byte vectors.  Otherwise one
+// load per slot, all issued together.  `wanted` is wave-uniform: a wave without a valid slot
+// does not touch the payload.
+template <typename ElemT, bool ONE>
+__device__ __forceinline__ void narrow_load(const ReduceArgs& a, int64_t s0, int d, bool wanted,
+                                            ElemT (&raw)[kSlotsPerLane])
 {
     constexpr int SPL = kSlotsPerLane;
-    const int64_t esize = (int64_t)sizeof(ElemT);
-    const int D = a.feat_dim;
-    if (early.used) {
+    constexpr int NV = SPL * (int)sizeof(ElemT) / 16;
 #pragma unroll
-        for (int k = 0; k < SPL / 4; ++k) {
-            union { vec16 v; ElemT e[4]; } u;
-            u.v = early.raw[k];
+    for (int j = 0; j < SPL; ++j) raw[j] = ElemT{};
+    if (!wanted) return;
+    const int64_t left = a.total_slots - s0;             // slots from the lane's first one to the end
+    if (ONE && left >= SPL) {
+        union { vec16 v[NV]; ElemT e[SPL]; } u;
+        const vec16* from = reinterpret_cast<const vec16*>(a.packed + s0 * (int64_t)sizeof(ElemT));
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                x[4 * k + j] = ((vmask >> (4 * k + j)) & 1u) ? Elem<ElemT>::get(u.e[j]) : (Acc)0;
-        }
+        for (int k = 0; k < NV; ++k) u.v[k] = load_stream(from + k);
+#pragma unroll
+        for (int j = 0; j < SPL; ++j) raw[j] = u.e[j];
     } else {
+        const int64_t stride = (int64_t)(ONE ? 1 : a.feat_dim) * (int64_t)sizeof(ElemT);
+        const uint8_t* from = a.packed + (s0 * (ONE ? 1 : a.feat_dim) + d) * (int64_t)sizeof(ElemT);
 #pragma unroll
-        for (int j = 0; j < SPL; ++j) {
-            x[j] = 0;
-            if ((vmask >> j) & 1u)
-                x[j] = Elem<ElemT>::get(*reinterpret_cast<const ElemT*>(
-                    a.packed + ((s0 + j) * D + d) * esize));
-        }
+        for (int j = 0; j < SPL; ++j)
+            if (j < left) raw[j] = *reinterpret_cast<const ElemT*>(from + j * stride);
     }
 }
 
@@ -606,17 +585,16 @@ __device__ __forceinline__ void narrow_emit(const ReduceArgs& a, int64_t q, int 
     }
 }
 
-// Floating-point sums: segmented scan (only additions of the segment's own
-// terms, so no cancellation against neighbouring segments).
-template <typename ElemT>
+template <typename ElemT, bool ONE>
 __global__ __launch_bounds__(kThreads) void reduce_narrow_kernel(ReduceArgs a)
 {
     typedef typename Elem<ElemT>::Acc Acc;
     constexpr int NW = kThreads / kWave;
     constexpr int SPL = kSlotsPerLane;
-    __shared__ Acc s_wave_sum[NW];         // sum behind the wave's last break (whole wave if none)
-    __shared__ int32_t s_wave_any[NW];     // the wave holds a break
-    __shared__ int32_t s_wave_start[NW];
+    __shared__ Acc s_wave_sum[NW];                     // the wave's sum behind its last break (all of it if none)
+    __shared__ uint32_t s_wave_any[NW];                // the wave holds a break
+    __shared__ unsigned long long s_wave_breaks[NW];   // which lanes of the wave hold a break
+    __shared__ int32_t s_last_break[kThreads];         // position of a lane's last break (lanes that have one)
     __shared__ ChunkDesc s_desc;
 
     const int tid = (int)threadIdx.x;
@@ -627,122 +605,57 @@ __global__ __launch_bounds__(kThreads) void reduce_narrow_kernel(ReduceArgs a)
     const int pos0 = tid * SPL;
     const int64_t s0 = g0 + pos0;
     if (tid == 0) s_desc = ChunkDesc{kHeadNone, 0, 0, -1};
-    const NarrowEarly early = narrow_load_early<ElemT>(a, s0);
-    const LaneSegments seg = narrow_lane_segments(a, g0, g1, s_wave_start);
-    const uint32_t bmask = seg.bmask;
+    const LaneFlags f = narrow_lane_flags(a, g0, g1);
+    const uint32_t bmask = f.bmask;
+    const unsigned long long wave_breaks = __ballot(bmask != 0);
+    const bool wave_valid = __ballot(f.vmask != 0) != 0;
+    const int last_break = bmask ? 31 - __clz((int)bmask) : 0;
+    if (bmask) s_last_break[tid] = pos0 + last_break;
+    if (lane == 0) s_wave_breaks[wave] = wave_breaks;
+    const uint32_t from_last_break = f.vmask & (~0u << last_break);   // the lane's part of the open segment
+    const bool finishes = f.ends != 0 || f.tail_open;                 // a piece ends in this lane
+    int32_t prev_start = -1;           // position of the last break in front of this lane, -1: none in the tile
 
-    for (int d = 0; d < a.feat_dim; ++d) {
-        Acc incl[SPL];
-        narrow_load<ElemT, Acc>(a, s0, d, seg.vmask, early, incl);
-        Acc run = 0;
+    const int n_feat = ONE ? 1 : a.feat_dim;
+    for (int d = 0; d < n_feat; ++d) {
+        ElemT raw[SPL];
+        narrow_load<ElemT, ONE>(a, s0, d, wave_valid, raw);
+        Acc tail = 0;
 #pragma unroll
-        for (int j = 0; j < SPL; ++j) {
-            if ((bmask >> j) & 1u) run = 0;
-            run += incl[j];
-            incl[j] = run;
-        }
-        // carry from the lanes before this one: wave scan, then the waves before
-        SegState<Acc> scan{run, bmask != 0 ? 1 : 0};
-#pragma unroll
-        for (int dd = 1; dd < kWave; dd <<= 1) {
-            const SegState<Acc> left = seg_shfl_up(scan, dd);
-            if (lane >= dd) scan = seg_combine(left, scan);
-        }
-        SegState<Acc> carry = seg_shfl_up(scan, 1);
-        if (lane == 0) carry = SegState<Acc>{0, 0};
+        for (int j = 0; j < SPL; ++j) tail += ((from_last_break >> j) & 1u) ? Elem<ElemT>::get(raw[j]) : (Acc)0;
+        const SegState<Acc> scan = wave_scan(SegState<Acc>{tail, bmask != 0 ? 1u : 0u}, SegCombine<Acc>(),
+                                             SegMove<Acc>());
+        SegState<Acc> carry = SegMove<Acc>().template at<kDppWaveShr1, 0xF>(scan);    // the lanes before this one
         if (d > 0) __syncthreads();                  // the previous feature's wave sums are consumed
         if (lane == kWave - 1) { s_wave_sum[wave] = scan.sum; s_wave_any[wave] = scan.any; }
         __syncthreads();
+        if (!finishes) continue;
+
+        // the segments that end in this lane, and the open tail of the tile
         SegState<Acc> before{0, 0};
         for (int w = 0; w < wave; ++w)
-            before = seg_combine(before, SegState<Acc>{s_wave_sum[w], s_wave_any[w]});
-        carry = seg_combine(before, carry);
-
-        // the segments that end in this lane (rare), and the open tail of the tile
-        if (seg.ends != 0 || seg.tail_open) {
-#pragma unroll
-            for (int j = 0; j < SPL; ++j) {
-                const bool is_end = (seg.ends >> j) & 1u;
-                if (!is_end && !(seg.tail_open && j == seg.j_last)) continue;
-                const uint32_t upto = bmask & ((2u << j) - 1u);          // breaks at or before j
-                const Acc sum = upto ? incl[j] : carry.sum + incl[j];
-                const int32_t start = upto ? pos0 + (31 - __clz((int)upto)) : seg.prev_start;
-                const int32_t cnt = start >= 0 ? pos0 + j - start + 1 : pos0 + j + 1;
-                narrow_emit<Acc>(a, q, d, g0 + max(start, 0), is_end, start >= 0, sum, cnt, &s_desc);
+            before = SegCombine<Acc>()(before, SegState<Acc>{s_wave_sum[w], s_wave_any[w]});
+        carry = SegCombine<Acc>()(before, carry);
+        if (d == 0) {
+            const unsigned long long lower = wave_breaks & ((1ull << lane) - 1ull);
+            int holder = lower ? wave * kWave + 63 - __clzll((long long)lower) : -1;
+            for (int w = wave - 1; w >= 0 && holder < 0; --w) {
+                const unsigned long long b = s_wave_breaks[w];
+                if (b) holder = w * kWave + 63 - __clzll((long long)b);
             }
+            if (holder >= 0) prev_start = s_last_break[holder];
         }
-    }
-    __syncthreads();
-    if (tid == 0 && a.desc) a.desc[q] = s_desc;
-}
-
-// Integer sums are exact, so a segment's sum can be taken as a difference of
-// plain prefix sums: the common path is one unsegmented scan of the lanes'
-// totals, and only a lane in which a segment ends (rare when segments are long)
-// looks up the prefix in front of the segment's first slot: the exclusive prefix
-// of the lane that holds it plus the few elements before it, both kept in LDS.
-__global__ __launch_bounds__(kThreads) void reduce_narrow_int_kernel(ReduceArgs a)
-{
-    typedef long long Acc;
-    constexpr int NW = kThreads / kWave;
-    constexpr int SPL = kSlotsPerLane;
-    __shared__ Acc s_lane_excl[kThreads];  // prefix sum in front of each lane, inside its wave
-    __shared__ int32_t s_x[kNarrowTile];   // the tile's elements of the current feature, 0 where not valid
-    __shared__ Acc s_wave_total[NW];
-    __shared__ int32_t s_wave_start[NW];
-    __shared__ ChunkDesc s_desc;
-
-    const int tid = (int)threadIdx.x;
-    const int lane = lane_id(), wave = wave_id();
-    const int64_t q = blockIdx.x;
-    const int64_t g0 = q * kNarrowTile;
-    const int64_t g1 = min(a.total_slots, g0 + kNarrowTile);
-    const int pos0 = tid * SPL;
-    const int64_t s0 = g0 + pos0;
-    const int D = a.feat_dim;
-    if (tid == 0) s_desc = ChunkDesc{kHeadNone, 0, 0, -1};
-    const NarrowEarly early = narrow_load_early<int32_t>(a, s0);
-    const LaneSegments seg = narrow_lane_segments(a, g0, g1, s_wave_start);
-
-    for (int d = 0; d < D; ++d) {
-        Acc x[SPL];
-        narrow_load<int32_t, Acc>(a, s0, d, seg.vmask, early, x);
-        Acc total = 0;
+        Acc run = carry.sum;
+        int32_t start = prev_start;
 #pragma unroll
-        for (int j = 0; j < SPL; ++j) total += x[j];
-        Acc incl = total;
-#pragma unroll
-        for (int dd = 1; dd < kWave; dd <<= 1) {
-            const Acc left = shfl_up_acc(incl, dd);
-            if (lane >= dd) incl += left;
-        }
-        if (d > 0) __syncthreads();                  // the previous feature's prefixes are consumed
-#pragma unroll
-        for (int j = 0; j < SPL; ++j) s_x[pos0 + j] = (int32_t)x[j];
-        s_lane_excl[tid] = incl - total;
-        if (lane == kWave - 1) s_wave_total[wave] = incl;
-        __syncthreads();
-
-        // segments that end in this lane, and the open tail of the tile
-        uint32_t todo = seg.ends | (seg.tail_open ? 1u << seg.j_last : 0u);
-        while (todo) {
-            const int j = __ffs((int)todo) - 1;
-            todo &= todo - 1;
-            // prefix sum of the tile in front of tile-relative position p
-            auto prefix_before = [&](int32_t p) {
-                const int owner = min(p / SPL, kThreads - 1);
-                Acc sum = s_lane_excl[owner];
-                for (int w = 0; w < owner / kWave; ++w) sum += s_wave_total[w];
-                for (int i = owner * SPL; i < p; ++i) sum += s_x[i];
-                return sum;
-            };
-            const bool is_end = (seg.ends >> j) & 1u;
-            const uint32_t upto = seg.bmask & ((2u << j) - 1u);          // breaks at or before j
-            const int32_t start = upto ? pos0 + (31 - __clz((int)upto)) : seg.prev_start;
-            const Acc upto_end = prefix_before(pos0 + j + 1);
-            const Acc sum = start >= 0 ? upto_end - prefix_before(start) : upto_end;
-            const int32_t cnt = start >= 0 ? pos0 + j - start + 1 : pos0 + j + 1;
-            narrow_emit<Acc>(a, q, d, g0 + max(start, 0), is_end, start >= 0, sum, cnt, &s_desc);
+        for (int j = 0; j < SPL; ++j) {
+            if ((bmask >> j) & 1u) { run = 0; start = pos0 + j; }
+            if ((f.vmask >> j) & 1u) run += Elem<ElemT>::get(raw[j]);
+            const bool is_end = (f.ends >> j) & 1u;
+            if (is_end || (f.tail_open && j == f.j_last)) {
+                const int32_t cnt = start >= 0 ? pos0 + j - start + 1 : pos0 + j + 1;
+                narrow_emit<Acc>(a, q, d, g0 + max(start, 0), is_end, start >= 0, run, cnt, &s_desc);
+            }
         }
     }
     __syncthreads();
@@ -884,11 +797,11 @@ static void launch_reduce(const ReducePlan& p, const ReduceArgs& a, hipStream_t 
     if (p.wide) {
         launch_wide<ElemT>(p, a, stream);
     } else {
-        if (sizeof(ElemT) == 4 && sizeof(Acc) == 8)
-            hipLaunchKernelGGL(reduce_narrow_int_kernel, dim3((uint32_t)p.total_chunks), dim3(kThreads),
-                               0, stream, a);
+        if (a.feat_dim == 1)
+            hipLaunchKernelGGL((reduce_narrow_kernel<ElemT, true>), dim3((uint32_t)p.total_chunks),
+                               dim3(kThreads), 0, stream, a);
         else
-            hipLaunchKernelGGL(reduce_narrow_kernel<ElemT>, dim3((uint32_t)p.total_chunks),
+            hipLaunchKernelGGL((reduce_narrow_kernel<ElemT, false>), dim3((uint32_t)p.total_chunks),
                                dim3(kThreads), 0, stream, a);
     }
     if (p.partials) {

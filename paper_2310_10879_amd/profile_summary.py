@@ -11,14 +11,14 @@ repository root on the MI355X; `--calibrate-copy` adds a plain 1 GiB elementwise
 whose known size scales the two HBM counters):
 
     rocprofv3 --kernel-trace --stats --output-format csv -d $OUT/kt -o kt -- \
-        python3 bench.py --workload W --steps 10 --warmup 2 --no-cpu-baseline --calibrate-copy
+        python3 bench.py --workload W --steps 10 --warmup 2 --only --no-cpu-baseline --calibrate-copy
     rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d $OUT/fetch -o fetch -- \
-        python3 bench.py --workload W --steps 3 --warmup 1 --no-cpu-baseline --calibrate-copy
+        python3 bench.py --workload W --steps 3 --warmup 1 --only --no-cpu-baseline --calibrate-copy
     rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d $OUT/write -o write -- \
-        python3 bench.py --workload W --steps 3 --warmup 1 --no-cpu-baseline --calibrate-copy
+        python3 bench.py --workload W --steps 3 --warmup 1 --only --no-cpu-baseline --calibrate-copy
 
-Writes profiles/bload_workloadW_kernel_trace.md, profiles/bload_pack_workloadW_hbm_counters.md
-and profiles/bload_pack_workloadW_hbm_traffic.json (read back by bench.py for `roofline.traffic`).
+Writes profiles/bload_workloadW_kernel_trace.md, profiles/bload_workloadW_hbm_counters.md
+and profiles/bload_workloadW_hbm_traffic.json (read back by bench.py for the `traffic` fields).
 """
 from __future__ import annotations
 
@@ -71,7 +71,7 @@ def main() -> None:
     lines = [f"# rocprofv3 kernel trace of bench.py, workload {cfg}", "",
              "Command (on the MI355X, from the repository root; OUT = a scratch directory):", "",
              "    rocprofv3 --kernel-trace --stats --output-format csv -d $OUT/kt -o kt -- \\",
-             f"        python3 bench.py --workload {w} --steps 10 --warmup 2 --no-cpu-baseline --calibrate-copy{flags}",
+             f"        python3 bench.py --workload {w} --steps 10 --warmup 2 --only --no-cpu-baseline --calibrate-copy{flags}",
              "", "Summarised by `python -m paper_2310_10879_amd.profile_summary` from kt_kernel_stats.csv.", "",
              "| kernel | calls | avg ns | min ns | max ns | % of GPU time |", "|---|---|---|---|---|---|"]
     with open(args.trace) as f:
@@ -79,15 +79,14 @@ def main() -> None:
             lines.append(f"| {short(r['Name'])} | {r['Calls']} | {float(r['AverageNs']):.0f} | {r['MinNs']} | "
                          f"{r['MaxNs']} | {float(r['Percentage']):.2f} |")
     ph = bench["phases_ms"]
-    lines += ["", f"bench.py's event timing in the same run (ms per call): plan {ph['plan']:.4f}, "
-              f"pack {ph['pack']:.4f}, segment_reduce {ph['segment_reduce']:.4f}"
-              + (f", segment_scan {ph['segment_scan']:.4f}" if "segment_scan" in ph else "") + "; "
-              f"pack roofline: {bench['roofline']['achieved']:.0f} GB/s of algorithmic bytes = "
-              f"{100 * bench['roofline']['frac']:.1f} % of {bench['roofline']['peak']:.0f} GB/s."]
-    if "segment_scan" in bench:
-        lines += [f"segment_scan: {bench['segment_scan']['algorithmic_GBps']:.0f} GB/s of algorithmic bytes "
-                  f"({bench['segment_scan']['algorithmic_bytes_per_launch'] / 1e9:.3f} GB per call: valid payload read, "
-                  "every output element and both flag planes)."]
+    lines += ["", "bench.py's event timing in the same run (ms per call): "
+              + ", ".join(f"{name} {ms:.4f}" for name, ms in ph.items()) + "."]
+    for name in ("pack", "segment_reduce", "segment_scan"):
+        if name in bench:
+            r = bench[name]
+            lines += [f"{name}: {r['algorithmic_bytes_per_launch'] / 1e9:.4f} GB of algorithmic bytes per call / "
+                      f"{r['launch_ms']:.4f} ms = {r['achieved']:.0f} GB/s = {100 * r['frac']:.1f} % of "
+                      f"{r['peak']:.0f} GB/s."]
     with open(os.path.join(ROOT, "profiles", f"bload_workload{w}{tag}_kernel_trace.md"), "w") as f:
         f.write("\n".join(lines) + "\n")
     if not args.fetch or not args.write:
@@ -99,45 +98,59 @@ def main() -> None:
     cal = "torch mul (1 GiB calibration copy)"
     f_scale = CAL_KIB / fetch[(cal, "FETCH_SIZE")][0]
     w_scale = CAL_KIB / write[(cal, "WRITE_SIZE")][0]
-    pack_kernel = "bload::" + bench["roofline"]["kernel"]
-    alg = bench["roofline"]["algorithmic_bytes_per_launch"]
-    rows = ["| kernel | FETCH_SIZE KiB (raw) | read GB (scaled) | WRITE_SIZE KiB (raw) | written GB (scaled) |",
-            "|---|---|---|---|---|"]
-    traffic = None
+    rows = ["| kernel | dispatches | FETCH_SIZE KiB (raw) | read GB (scaled) | WRITE_SIZE KiB (raw) | written GB (scaled) |",
+            "|---|---|---|---|---|---|"]
+    # kernel families of one library call each: (bench key, kernel name prefix, main kernel prefixes, source file)
+    families = {"pack": ("pack", "bload::pack_", ("bload::pack_wide", "bload::pack_narrow"), "bload_pack.hip"),
+                "reduce": ("segment_reduce", "bload::reduce_", ("bload::reduce_wide", "bload::reduce_narrow"),
+                           "bload_reduce.hip"),
+                "scan": ("segment_scan", "bload::scan_", ("bload::scan_apply",), "bload_scan.hip")}
+    totals = {k: [0.0, 0.0, 0] for k in families}          # read bytes, written bytes, calls
     names = sorted({k[0] for k in fetch} | {k[0] for k in write})
     for name in names:
         if not (name.startswith("bload::") or name == cal):
             continue
-        fr = fetch.get((name, "FETCH_SIZE"), (0.0, 0))[0]
-        wr = write.get((name, "WRITE_SIZE"), (0.0, 0))[0]
+        fr, n_f = fetch.get((name, "FETCH_SIZE"), (0.0, 0))
+        wr, n_w = write.get((name, "WRITE_SIZE"), (0.0, 0))
         rd_b, wr_b = fr * f_scale * 1024, wr * w_scale * 1024
+        for fam, (_, prefix, mains, _) in families.items():
+            if name.startswith(prefix):
+                totals[fam][0] += rd_b * n_f
+                totals[fam][1] += wr_b * n_w
+                if name.startswith(mains):
+                    totals[fam][2] += n_f
         if rd_b + wr_b < 1e6:
             continue
-        rows.append(f"| {name} | {fr:.1f} | {rd_b / 1e9:.4f} | {wr:.1f} | {wr_b / 1e9:.4f} |")
-        if name.startswith(pack_kernel):
-            traffic = rd_b + wr_b
+        rows.append(f"| {name} | {n_f} | {fr:.1f} | {rd_b / 1e9:.4f} | {wr:.1f} | {wr_b / 1e9:.4f} |")
     out = [f"# rocprofv3 HBM counters of bench.py, workload {cfg}", "",
            "Two counter passes, each a run of its own (on the MI355X, from the repository root; OUT = a scratch directory):", "",
            "    rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d $OUT/fetch -o fetch -- \\",
-           f"        python3 bench.py --workload {w} --steps 3 --warmup 1 --no-cpu-baseline --calibrate-copy",
+           f"        python3 bench.py --workload {w} --only --steps 3 --warmup 1 --no-cpu-baseline --calibrate-copy",
            "    rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d $OUT/write -o write -- \\",
-           f"        python3 bench.py --workload {w} --steps 3 --warmup 1 --no-cpu-baseline --calibrate-copy",
+           f"        python3 bench.py --workload {w} --only --steps 3 --warmup 1 --no-cpu-baseline --calibrate-copy",
            "", "Mean per dispatch.  Scale factors from the calibration copy (known: 1048576 KiB read, 1048576 KiB",
-           f"written): FETCH_SIZE x {f_scale:.5f}, WRITE_SIZE x {w_scale:.5f}.", ""] + rows
-    if traffic is not None:
-        out += ["", f"{pack_kernel}: {traffic / 1e9:.4f} GB of HBM traffic per launch against {alg / 1e9:.4f} GB of "
-                f"algorithmic bytes ({100 * (traffic / alg - 1):+.2f} %)."]
-        src = os.path.join(ROOT, "paper_2310_10879_amd", "csrc", "bload_pack.hip")
-        with open(src, "rb") as f:
+           f"written): FETCH_SIZE x {f_scale:.5f}, WRITE_SIZE x {w_scale:.5f}.", ""] + rows + [""]
+    record = {"workload": w, "fetch_scale": f_scale, "write_scale": w_scale, "families": {}}
+    for fam, (key, _, _, source) in families.items():
+        rd, wr, calls = totals[fam]
+        if calls == 0 or key not in bench:
+            continue
+        rd, wr = rd / calls, wr / calls
+        alg = bench[key]["algorithmic_bytes_per_launch"]
+        out += [f"{key} (all its kernels, per call): {rd / 1e9:.4f} GB read + {wr / 1e9:.4f} GB written = "
+                f"{(rd + wr) / 1e9:.4f} GB of HBM traffic against {alg / 1e9:.4f} GB of algorithmic bytes "
+                f"({100 * ((rd + wr) / alg - 1):+.2f} %)."]
+        with open(os.path.join(ROOT, "paper_2310_10879_amd", "csrc", source), "rb") as f:
             digest = hashlib.sha256(f.read()).hexdigest()
-        with open(os.path.join(ROOT, "profiles", f"bload_pack_workload{w}_hbm_traffic.json"), "w") as f:
-            json.dump({"workload": w, "kernel": pack_kernel, "hbm_bytes_per_launch": traffic,
-                       "algorithmic_bytes_per_launch": alg, "fetch_scale": f_scale, "write_scale": w_scale,
-                       "kernel_source_sha256": digest}, f, indent=1)
-            f.write("\n")
-    with open(os.path.join(ROOT, "profiles", f"bload_pack_workload{w}_hbm_counters.md"), "w") as f:
+        record["families"][fam] = {"hbm_bytes_per_call": rd + wr, "read_bytes_per_call": rd,
+                                   "written_bytes_per_call": wr, "algorithmic_bytes_per_call": alg,
+                                   "source": source, "source_sha256": digest}
+    with open(os.path.join(ROOT, "profiles", f"bload_workload{w}_hbm_traffic.json"), "w") as f:
+        json.dump(record, f, indent=1)
+        f.write("\n")
+    with open(os.path.join(ROOT, "profiles", f"bload_workload{w}_hbm_counters.md"), "w") as f:
         f.write("\n".join(out) + "\n")
-    print("\n".join(lines[-1:] + out[-1:]))
+    print("\n".join(lines[-3:] + out[-3:]))
 
 
 if __name__ == "__main__":

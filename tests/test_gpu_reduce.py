@@ -178,8 +178,8 @@ def assert_sum_accuracy(got, src, so, L, D, op, ulps):
 @pytest.mark.parametrize("n,T,D,ulps", [(48, 3000, 80, 12),      # lanes across features, many chunks + stitch
                                         (300, 3000, 80, 12),     # fewer chunks per block
                                         (6, 3000, 2048, 12),     # a wave per row
-                                        (40, 30000, 1, 32),      # lanes across time, 15 tiles per sequence
-                                        (64, 3000, 3, 32)])
+                                        (40, 30000, 1, 48),      # lanes across time, 8 tiles per sequence
+                                        (64, 3000, 3, 48)])
 @pytest.mark.parametrize("op", ["sum", "mean"])
 def test_reduce_float32_sums_hold_at_any_length(n, T, D, ulps, op):
     bl = binding()
