@@ -27,6 +27,8 @@
 #include <hip/hip_fp16.h>
 #include <limits.h>
 
+#include <algorithm>
+
 namespace bload {
 
 constexpr int kHeadNone = 0, kHeadClosed = 1, kHeadThrough = 2;
@@ -51,7 +53,11 @@ struct ReduceArgs {
     int32_t feat_dim;
     int32_t n_seq;
     int32_t mean;            // 1: divide by the frame count
-    double inv_t_blk;        // 1.0 / t_blk
+    // narrow: a block is cut into `n_chunks` tiles (t_blk >= the tile), or a tile holds
+    // `blocks_per_tile` whole blocks (t_blk < the tile); magic_t_blk = min(ceil(2^32 / t_blk),
+    // 2^32 - 1) then divides positions inside a tile by t_blk (to within one, fixed up)
+    int32_t blocks_per_tile;
+    uint32_t magic_t_blk;
     void* out;               // [n_seq, feat_dim] float or int64
     // chunking
     int32_t chunk;           // slots per chunk
@@ -420,6 +426,16 @@ struct SegCombine {
 };
 
 template <typename Acc>
+struct PlainSum {
+    __device__ __forceinline__ Acc operator()(Acc left, Acc right) const { return left + right; }
+};
+template <typename Acc>
+struct PlainMove {
+    template <int CTRL, int ROW_MASK>
+    __device__ __forceinline__ Acc at(Acc x) const { return dpp_move<CTRL, ROW_MASK>(x, (Acc)0); }
+};
+
+template <typename Acc>
 struct SegMove {
     template <int CTRL, int ROW_MASK>
     __device__ __forceinline__ SegState<Acc> at(SegState<Acc> s) const
@@ -431,15 +447,42 @@ struct SegMove {
 // Bit j of the result: byte j of the 16 flag bytes is non-zero.
 __device__ __forceinline__ uint32_t nonzero_bytes16(vec16 w)
 {
-    uint32_t m = 0;
+    // 0x80 in every non-zero byte; a dot product with byte weights 1, 2, 4, 8 (16 ... 128 for the
+    // next four bytes) then puts one bit per byte side by side, seven places up
+    uint32_t t[4];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const uint32_t x = w[k];
-        // top bit of every non-zero byte, then bits 7, 15, 23, 31 -> bits 0 .. 3
-        const uint32_t t = ((((x & 0x7f7f7f7fu) + 0x7f7f7f7fu) | x) & 0x80808080u) >> 7;
-        m |= ((t | (t >> 7) | (t >> 14) | (t >> 21)) & 0xFu) << (4 * k);
+    for (int k = 0; k < 4; ++k) t[k] = (((w[k] & 0x7f7f7f7fu) + 0x7f7f7f7fu) | w[k]) & 0x80808080u;
+    const uint32_t lo = __builtin_amdgcn_udot4(t[1], 0x80402010u, __builtin_amdgcn_udot4(t[0], 0x08040201u, 0u, false), false);
+    const uint32_t hi = __builtin_amdgcn_udot4(t[3], 0x80402010u, __builtin_amdgcn_udot4(t[2], 0x08040201u, 0u, false), false);
+    return (lo >> 7) | ((hi >> 7) << 8);
+}
+
+typedef vec16 __attribute__((aligned(1))) vec16_any;      // a 16-byte vector at any address
+
+// Where a workgroup's tile lies.  Tiles never straddle a block: a tile is a piece of one block
+// (blocks of at least a tile's length) or a whole number of blocks.
+struct NarrowTile {
+    int64_t g0;            // first slot
+    int32_t n;             // slots in the tile
+    int32_t rem0;          // position of the tile's first slot inside its block
+};
+
+__device__ __forceinline__ NarrowTile narrow_tile(const ReduceArgs& a, int64_t q)
+{
+    NarrowTile t;
+    if (a.t_blk >= kNarrowTile) {
+        const int64_t b = a.n_chunks == 1 ? q : (int64_t)((uint32_t)q / (uint32_t)a.n_chunks);
+        const int32_t c = (int32_t)(q - b * a.n_chunks);
+        t.rem0 = c * kNarrowTile;
+        t.g0 = b * (int64_t)a.t_blk + t.rem0;
+        t.n = min(kNarrowTile, a.t_blk - t.rem0);
+    } else {
+        const int64_t b0 = q * a.blocks_per_tile;
+        t.rem0 = 0;
+        t.g0 = b0 * (int64_t)a.t_blk;
+        t.n = (int32_t)min((int64_t)a.blocks_per_tile, a.num_blocks - b0) * a.t_blk;
     }
-    return m;
+    return t;
 }
 
 // What a lane knows about its 16 slots after reading the flags.
@@ -453,55 +496,69 @@ struct LaneFlags {
 
 // Reads the flags of the lane's slots and of its neighbours and derives the masks.  Called by
 // every thread of the workgroup (the lanes of a wave exchange their border slots).
-__device__ __forceinline__ LaneFlags narrow_lane_flags(const ReduceArgs& a, int64_t g0, int64_t g1)
+__device__ __forceinline__ LaneFlags narrow_lane_flags(const ReduceArgs& a, const NarrowTile& tile)
 {
     constexpr int SPL = kSlotsPerLane;
     constexpr uint32_t ALL = (1u << SPL) - 1u;
     const int tid = (int)threadIdx.x;
     const int lane = lane_id();
-    const int64_t S = a.total_slots;
     const uint32_t T = (uint32_t)a.t_blk;
     const int pos0 = tid * SPL;
-    const int64_t s0 = g0 + pos0;
-    const int64_t sn = s0 + SPL;                         // the slot after this lane's last one
+    const int32_t left = tile.n - pos0;                  // slots from this lane's first one to the tile's end
+    const int64_t s0 = tile.g0 + pos0;
     LaneFlags r;
 
-    uint8_t before_valid = 0, after_valid = 0, after_reset = 0;
-    if (lane == 0 && s0 > 0 && s0 <= S) before_valid = a.valid[s0 - 1];
-    if (lane == kWave - 1 && sn < S) { after_valid = a.valid[sn]; after_reset = a.reset[sn]; }
+    // position of the lane's first slot inside its block, and of the slot behind its last one
+    uint32_t rem0 = (uint32_t)tile.rem0 + (uint32_t)pos0;
+    if (T < (uint32_t)kNarrowTile) {
+        rem0 -= __umulhi((uint32_t)pos0, a.magic_t_blk) * T;        // pos0 mod T, possibly one T too many
+        if (rem0 >= T) rem0 -= T;
+    }
+    uint32_t rem_next = rem0 + (uint32_t)SPL;
+    while (rem_next >= T) rem_next -= T;                 // at most once unless t_blk < 16
 
+    // the slots in front of and behind the lanes of this wave, where they belong to the same block
+    uint8_t before_valid = 0, after_valid = 0, after_reset = 0;
+    if (lane == 0 && rem0 != 0 && left > 0) before_valid = a.valid[s0 - 1];
+    if (lane == kWave - 1 && rem_next != 0 && left >= SPL) { after_valid = a.valid[s0 + SPL]; after_reset = a.reset[s0 + SPL]; }
+
+    static_assert(SPL == 16, "the flags of a lane are one 16-byte vector per plane");
+    const bool whole = left >= SPL;                      // all 16 slots lie in the tile
+    vec16 uv = {0u, 0u, 0u, 0u}, ur = {0u, 0u, 0u, 0u};
+    if (whole) {
+        uv = __builtin_nontemporal_load(reinterpret_cast<const vec16_any*>(a.valid + s0));
+        ur = __builtin_nontemporal_load(reinterpret_cast<const vec16_any*>(a.reset + s0));
+    }
+    // Two kinds of waves are common in packed blocks and need no byte-by-byte look at their
+    // flags: nothing but padding (block tails), and nothing but valid slots without a start flag
+    // (the inside of long sequences).  Both tests are wave-uniform.
+    const uint32_t v_any = uv[0] | uv[1] | uv[2] | uv[3], v_all = uv[0] & uv[1] & uv[2] & uv[3];
+    const uint32_t r_any = ur[0] | ur[1] | ur[2] | ur[3];
+    const bool lane_blank = whole ? v_any == 0u : left <= 0;
+    // (a non-zero byte in the AND of the four words means four non-zero bytes)
+    const bool lane_plain = whole && r_any == 0u &&
+                            ((((v_all & 0x7f7f7f7fu) + 0x7f7f7f7fu) | v_all) & 0x80808080u) == 0x80808080u;
     uint32_t vmask = 0, rmask = 0;
-    if (sn <= S) {
-        static_assert(SPL == 16, "the flags of a lane are one 16-byte vector per plane");
-        const vec16 uv = load_stream(reinterpret_cast<const vec16*>(a.valid + s0));
-        const vec16 ur = load_stream(reinterpret_cast<const vec16*>(a.reset + s0));
+    if (__ballot(lane_blank) == ~0ull) {
+        // vmask = rmask = 0
+    } else if (__ballot(lane_plain) == ~0ull) {
+        vmask = ALL;
+    } else if (whole) {
         vmask = nonzero_bytes16(uv);
         rmask = nonzero_bytes16(ur);
-    } else {
+    } else if (left > 0) {
+        // the tile ends inside this lane: slot by slot (those past the end re-read its last slot)
 #pragma unroll
         for (int j = 0; j < SPL; ++j) {
-            if (s0 + j < S) {
-                vmask |= (uint32_t)(a.valid[s0 + j] != 0) << j;
-                rmask |= (uint32_t)(a.reset[s0 + j] != 0) << j;
-            }
+            vmask |= (uint32_t)(a.valid[s0 + min(j, left - 1)] != 0) << j;
+            rmask |= (uint32_t)(a.reset[s0 + min(j, left - 1)] != 0) << j;
         }
+        vmask &= (1u << left) - 1u;
+        rmask &= (1u << left) - 1u;
     }
-    // first slots of blocks: slot index modulo T, from the tile's remainder (the
-    // quotient comes from a double reciprocal, fixed up exactly).  `gap` = slots
-    // from this lane's first one to the next block start.
+    // first slots of blocks among the lane's slots: `gap` = slots to the next block start
     uint32_t smask = 0;
-    uint32_t rem_next;                                   // (s0 + SPL) mod T
-    {
-        int64_t blk = (int64_t)((double)g0 * a.inv_t_blk);
-        if (blk * (int64_t)T > g0) --blk; else if ((blk + 1) * (int64_t)T <= g0) ++blk;
-        const uint32_t tile_rem = (uint32_t)(g0 - blk * (int64_t)T);
-        uint32_t rem0 = tile_rem + (uint32_t)pos0;
-        if (rem0 >= T) rem0 %= T;
-        uint32_t gap = rem0 == 0 ? 0u : T - rem0;
-        while (gap < (uint32_t)SPL) { smask |= 1u << gap; gap += T; }
-        rem_next = rem0 + (uint32_t)SPL;
-        if (rem_next >= T) rem_next %= T;
-    }
+    for (uint32_t gap = rem0 == 0 ? 0u : T - rem0; gap < (uint32_t)SPL; gap += T) smask |= 1u << gap;
     // validity of the slot before this lane's first one
     uint32_t prev_valid = dpp_move<kDppWaveShr1>((vmask >> (SPL - 1)) & 1u, 0u);
     if (lane == 0) prev_valid = (uint32_t)(before_valid != 0);
@@ -511,62 +568,103 @@ __device__ __forceinline__ LaneFlags narrow_lane_flags(const ReduceArgs& a, int6
     uint32_t next_first = dpp_move<kDppWaveShl1>(bmask & 1u, 0u);
     if (lane == kWave - 1) {
         next_first = 1u;
-        if (sn < S && rem_next != 0)
+        if (rem_next != 0 && left >= SPL)
             next_first = (!after_valid || after_reset || !((vmask >> (SPL - 1)) & 1u)) ? 1u : 0u;
     }
     const uint32_t next_brk = (bmask >> 1) | (next_first << (SPL - 1));
     r.vmask = vmask;
     r.bmask = bmask;
     r.ends = vmask & next_brk;
-    r.j_last = (int32_t)(g1 - 1 - s0);
+    r.j_last = left - 1;
     r.tail_open = r.j_last >= 0 && r.j_last < SPL && ((vmask >> r.j_last) & 1u) &&
                   !((next_brk >> r.j_last) & 1u);
     return r;
 }
 
-// The lane's 16 elements of feature d (whatever lies there; the caller masks them).  ONE: a
-// frame is one element, so they are contiguous and come as 16-byte vectors.  Otherwise one
-// load per slot, all issued together.  `wanted` is wave-uniform: a wave without a valid slot
-// does not touch the payload.
+// LDS staging of the payload of one workgroup: the 16-byte vectors of a lane, one spare vector
+// apart so that neighbouring lanes start in different banks.
+template <typename ElemT>
+struct NarrowStage {
+    static constexpr int NV = kSlotsPerLane * (int)sizeof(ElemT) / 16;     // vectors per lane
+    static constexpr int kStride = NV + 1;
+    static constexpr int kVectors = NV > 1 ? kThreads * kStride : 1;
+};
+
+// The lane's 16 elements of feature d; only those of valid slots mean anything.  ONE: a frame
+// is one element, so a wave's 1024 elements are contiguous: they are read as whole 1 KiB rows
+// (lane l takes vector l of each row) and handed to their lanes through LDS, because 64 lanes
+// that each read their own 64 bytes would touch four times as many cache lines per load.
+// Otherwise one load per slot, all issued together.  `left` = slots from the lane's first one
+// to the tile's end; `stage` = the workgroup's staging area (ONE only).
 template <typename ElemT, bool ONE>
-__device__ __forceinline__ void narrow_load(const ReduceArgs& a, int64_t s0, int d, bool wanted,
-                                            ElemT (&raw)[kSlotsPerLane])
+__device__ __forceinline__ void narrow_load(const ReduceArgs& a, int64_t s0, int32_t left, int d,
+                                            vec16* stage, ElemT (&raw)[kSlotsPerLane])
 {
     constexpr int SPL = kSlotsPerLane;
-    constexpr int NV = SPL * (int)sizeof(ElemT) / 16;
-#pragma unroll
-    for (int j = 0; j < SPL; ++j) raw[j] = ElemT{};
-    if (!wanted) return;
-    const int64_t left = a.total_slots - s0;             // slots from the lane's first one to the end
-    if (ONE && left >= SPL) {
+    constexpr int NV = NarrowStage<ElemT>::NV;
+    const int lane = lane_id();
+    // does the whole wave lie inside the tile (its last lane has all its slots)
+    const bool wave_whole = left - (kWave - 1 - lane) * SPL >= SPL;
+    if (ONE && NV > 1 && wave_whole) {
         union { vec16 v[NV]; ElemT e[SPL]; } u;
-        const vec16* from = reinterpret_cast<const vec16*>(a.packed + s0 * (int64_t)sizeof(ElemT));
+        const vec16_any* row = reinterpret_cast<const vec16_any*>(a.packed + (s0 - lane * SPL) * (int64_t)sizeof(ElemT));
+        vec16* mine = stage + (int)(threadIdx.x - lane) * NarrowStage<ElemT>::kStride;     // the wave's part
 #pragma unroll
-        for (int k = 0; k < NV; ++k) u.v[k] = load_stream(from + k);
+        for (int k = 0; k < NV; ++k) u.v[k] = __builtin_nontemporal_load(row + k * kWave + lane);
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            const int v = k * kWave + lane;                  // vector v of the wave belongs to lane v / NV
+            mine[(v / NV) * NarrowStage<ElemT>::kStride + (v % NV)] = u.v[k];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int k = 0; k < NV; ++k) u.v[k] = mine[lane * NarrowStage<ElemT>::kStride + k];
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int j = 0; j < SPL; ++j) raw[j] = u.e[j];
-    } else {
+    } else if (ONE && left >= SPL) {
+        union { vec16 v[NV > 0 ? NV : 1]; ElemT e[SPL]; } u;
+        const vec16_any* from = reinterpret_cast<const vec16_any*>(a.packed + s0 * (int64_t)sizeof(ElemT));
+#pragma unroll
+        for (int k = 0; k < NV; ++k) u.v[k] = __builtin_nontemporal_load(from + k);
+#pragma unroll
+        for (int j = 0; j < SPL; ++j) raw[j] = u.e[j];
+    } else if (left > 0) {
+        // slots past the tile's end re-read its last slot (their valid bits are 0)
         const int64_t stride = (int64_t)(ONE ? 1 : a.feat_dim) * (int64_t)sizeof(ElemT);
         const uint8_t* from = a.packed + (s0 * (ONE ? 1 : a.feat_dim) + d) * (int64_t)sizeof(ElemT);
 #pragma unroll
-        for (int j = 0; j < SPL; ++j)
-            if (j < left) raw[j] = *reinterpret_cast<const ElemT*>(from + j * stride);
+        for (int j = 0; j < SPL; ++j) raw[j] = *reinterpret_cast<const ElemT*>(from + min(j, left - 1) * stride);
+    } else {
+#pragma unroll
+        for (int j = 0; j < SPL; ++j) raw[j] = ElemT{};
     }
 }
 
+// x where bit j of `mask` is set, 0 (of the accumulator's type) elsewhere
+__device__ __forceinline__ float masked(float x, uint32_t mask, int j)
+{
+    return __int_as_float(__float_as_int(x) & (int32_t)__builtin_amdgcn_sbfe(mask, j, 1));
+}
+__device__ __forceinline__ long long masked(long long x, uint32_t mask, int j)
+{
+    return (long long)((int32_t)x & (int32_t)__builtin_amdgcn_sbfe(mask, j, 1));     // x holds an int32 here
+}
+
 // Hand one finished piece on: to the output row of its sequence, or to the
-// partial buffers when the tile border cuts its segment.  `slot` is the first
-// slot of the piece when the segment starts in this tile (`started`): the
-// sequence id is read there, as in the wide layout.
+// partial buffers when the tile border cuts its segment.  `seq` is the sequence
+// id at the first slot of the piece when the segment starts in this tile
+// (`started`), as in the wide layout.
 template <typename Acc>
-__device__ __forceinline__ void narrow_emit(const ReduceArgs& a, int64_t q, int d, int64_t slot,
+__device__ __forceinline__ void narrow_emit(const ReduceArgs& a, int64_t q, int d, int32_t seq,
                                             bool is_end, bool started, Acc sum, int32_t cnt,
                                             ChunkDesc* s_desc)
 {
     typedef typename OutOf<Acc>::T Out;
     const int D = a.feat_dim;
     if (is_end && started) {
-        const int32_t seq = a.seq_id[slot];
         if ((uint32_t)seq < (uint32_t)a.n_seq)
             static_cast<Out*>(a.out)[(int64_t)seq * D + d] = finish<Acc>(sum, cnt, a.mean);
     } else if (!started) {
@@ -580,7 +678,7 @@ __device__ __forceinline__ void narrow_emit(const ReduceArgs& a, int64_t q, int 
         if (a.tail_part) static_cast<Acc*>(a.tail_part)[q * D + d] = sum;
         if (d == 0) {
             s_desc->cnt_tail = cnt;
-            s_desc->seq_tail = a.seq_id[slot];
+            s_desc->seq_tail = seq;
         }
     }
 }
@@ -595,39 +693,61 @@ __global__ __launch_bounds__(kThreads) void reduce_narrow_kernel(ReduceArgs a)
     __shared__ uint32_t s_wave_any[NW];                // the wave holds a break
     __shared__ unsigned long long s_wave_breaks[NW];   // which lanes of the wave hold a break
     __shared__ int32_t s_last_break[kThreads];         // position of a lane's last break (lanes that have one)
+    __shared__ int32_t s_break_seq[kThreads];          // and the sequence id found there
+    __shared__ vec16 s_stage[ONE ? NarrowStage<ElemT>::kVectors : 1];
     __shared__ ChunkDesc s_desc;
 
     const int tid = (int)threadIdx.x;
     const int lane = lane_id(), wave = wave_id();
     const int64_t q = blockIdx.x;
-    const int64_t g0 = q * kNarrowTile;
-    const int64_t g1 = min(a.total_slots, g0 + kNarrowTile);
+    const NarrowTile tile = narrow_tile(a, q);
+    const int64_t g0 = tile.g0;
     const int pos0 = tid * SPL;
     const int64_t s0 = g0 + pos0;
     if (tid == 0) s_desc = ChunkDesc{kHeadNone, 0, 0, -1};
-    const LaneFlags f = narrow_lane_flags(a, g0, g1);
+    const LaneFlags f = narrow_lane_flags(a, tile);
     const uint32_t bmask = f.bmask;
     const unsigned long long wave_breaks = __ballot(bmask != 0);
-    const bool wave_valid = __ballot(f.vmask != 0) != 0;
+    const bool wave_valid = __ballot(f.vmask != 0) != 0;     // a wave without a valid slot reads no payload
     const int last_break = bmask ? 31 - __clz((int)bmask) : 0;
-    if (bmask) s_last_break[tid] = pos0 + last_break;
+    // the sequence that starts at the lane's last break: asked for now, so that the answer is
+    // there when a lane further on (or this one) closes that segment
+    int32_t own_seq = -1;
+    if (bmask && ((f.vmask >> last_break) & 1u)) own_seq = a.seq_id[s0 + last_break];
     if (lane == 0) s_wave_breaks[wave] = wave_breaks;
     const uint32_t from_last_break = f.vmask & (~0u << last_break);   // the lane's part of the open segment
     const bool finishes = f.ends != 0 || f.tail_open;                 // a piece ends in this lane
     int32_t prev_start = -1;           // position of the last break in front of this lane, -1: none in the tile
+    int32_t prev_seq = -1;             // and the sequence id found there
 
     const int n_feat = ONE ? 1 : a.feat_dim;
     for (int d = 0; d < n_feat; ++d) {
         ElemT raw[SPL];
-        narrow_load<ElemT, ONE>(a, s0, d, wave_valid, raw);
-        Acc tail = 0;
+        SegState<Acc> scan, carry;
+        Acc tail = 0;                  // the lane's slots from its last break on (all of them if it has none)
+        if (!wave_valid) {
+            // nothing but padding: every slot is a break, nothing to add
 #pragma unroll
-        for (int j = 0; j < SPL; ++j) tail += ((from_last_break >> j) & 1u) ? Elem<ElemT>::get(raw[j]) : (Acc)0;
-        const SegState<Acc> scan = wave_scan(SegState<Acc>{tail, bmask != 0 ? 1u : 0u}, SegCombine<Acc>(),
-                                             SegMove<Acc>());
-        SegState<Acc> carry = SegMove<Acc>().template at<kDppWaveShr1, 0xF>(scan);    // the lanes before this one
+            for (int j = 0; j < SPL; ++j) raw[j] = ElemT{};
+            scan = SegState<Acc>{0, 1u};
+            carry = SegState<Acc>{0, lane == 0 ? 0u : 1u};
+        } else if (wave_breaks == 0) {
+            // no break in the whole wave (so every slot is valid): plain sums
+            narrow_load<ElemT, ONE>(a, s0, tile.n - pos0, d, s_stage, raw);
+#pragma unroll
+            for (int j = 0; j < SPL; ++j) tail += Elem<ElemT>::get(raw[j]);
+            scan = SegState<Acc>{wave_scan(tail, PlainSum<Acc>(), PlainMove<Acc>()), 0u};
+            carry = SegState<Acc>{dpp_move<kDppWaveShr1>(scan.sum, (Acc)0), 0u};
+        } else {
+            narrow_load<ElemT, ONE>(a, s0, tile.n - pos0, d, s_stage, raw);
+#pragma unroll
+            for (int j = 0; j < SPL; ++j) tail += masked((Acc)Elem<ElemT>::get(raw[j]), from_last_break, j);
+            scan = wave_scan(SegState<Acc>{tail, bmask != 0 ? 1u : 0u}, SegCombine<Acc>(), SegMove<Acc>());
+            carry = SegMove<Acc>().template at<kDppWaveShr1, 0xF>(scan);      // the lanes before this one
+        }
         if (d > 0) __syncthreads();                  // the previous feature's wave sums are consumed
         if (lane == kWave - 1) { s_wave_sum[wave] = scan.sum; s_wave_any[wave] = scan.any; }
+        if (d == 0 && bmask) { s_last_break[tid] = pos0 + last_break; s_break_seq[tid] = own_seq; }
         __syncthreads();
         if (!finishes) continue;
 
@@ -643,19 +763,28 @@ __global__ __launch_bounds__(kThreads) void reduce_narrow_kernel(ReduceArgs a)
                 const unsigned long long b = s_wave_breaks[w];
                 if (b) holder = w * kWave + 63 - __clzll((long long)b);
             }
-            if (holder >= 0) prev_start = s_last_break[holder];
+            if (holder >= 0) { prev_start = s_last_break[holder]; prev_seq = s_break_seq[holder]; }
         }
-        Acc run = carry.sum;
-        int32_t start = prev_start;
+        // one piece per end (usually one per lane): the slots from the last break at or before the
+        // end -- or from the lane's first slot, behind the carried sum, if there is none -- up to it
+        uint32_t todo = f.ends | (f.tail_open ? 1u << f.j_last : 0u);
+        while (todo) {
+            const int j = 31 - __clz((int)todo);                          // last one first
+            todo &= ~(1u << j);
+            const uint32_t upto = bmask & ((2u << j) - 1u);               // breaks at or before j
+            const int lb = upto ? 31 - __clz((int)upto) : -1;
+            Acc sum = lb >= 0 ? (Acc)0 : carry.sum;
+            if (j == SPL - 1) {
+                sum += tail;        // the lane's last slot closes what its last break (or the carry) opened
+            } else {
+                const uint32_t piece = f.vmask & ((2u << j) - 1u) & (lb >= 0 ? ~0u << lb : ~0u);
 #pragma unroll
-        for (int j = 0; j < SPL; ++j) {
-            if ((bmask >> j) & 1u) { run = 0; start = pos0 + j; }
-            if ((f.vmask >> j) & 1u) run += Elem<ElemT>::get(raw[j]);
-            const bool is_end = (f.ends >> j) & 1u;
-            if (is_end || (f.tail_open && j == f.j_last)) {
-                const int32_t cnt = start >= 0 ? pos0 + j - start + 1 : pos0 + j + 1;
-                narrow_emit<Acc>(a, q, d, g0 + max(start, 0), is_end, start >= 0, run, cnt, &s_desc);
+                for (int k = 0; k < SPL; ++k) sum += masked((Acc)Elem<ElemT>::get(raw[k]), piece, k);
             }
+            const int32_t start = lb >= 0 ? pos0 + lb : prev_start;
+            const int32_t cnt = start >= 0 ? pos0 + j - start + 1 : pos0 + j + 1;
+            const int32_t seq = lb < 0 ? prev_seq : (lb == last_break ? own_seq : a.seq_id[s0 + lb]);
+            narrow_emit<Acc>(a, q, d, seq, (f.ends >> j) & 1u, start >= 0, sum, cnt, &s_desc);
         }
     }
     __syncthreads();
@@ -712,6 +841,7 @@ struct ReducePlan {
     int row_lanes_log2;
     int n_vec;
     int32_t chunk, n_chunks;
+    int32_t blocks_per_tile;  // narrow, t_blk < the tile: whole blocks per tile
     int64_t total_chunks;
     bool partials;           // can a chunk border cut a segment
     size_t desc_off, head_off, tail_off, bytes;
@@ -752,11 +882,19 @@ static ReducePlan reduce_plan(int64_t num_blocks, int32_t t_blk, int64_t feat_di
         p.total_chunks = num_blocks * p.n_chunks;
         p.partials = p.n_chunks > 1;
     } else {
+        // tiles never straddle a block: pieces of one block, or several whole blocks
         p.chunk = kNarrowTile;
-        p.n_chunks = 0;
-        p.total_chunks = ceil_div(num_blocks * (int64_t)t_blk, kNarrowTile);
-        // tiles that always end on a block border never cut a segment
-        p.partials = (kNarrowTile % t_blk) != 0;
+        if (t_blk >= kNarrowTile) {
+            p.n_chunks = (int32_t)ceil_div(t_blk, kNarrowTile);
+            p.blocks_per_tile = 1;
+            p.total_chunks = num_blocks * p.n_chunks;
+        } else {
+            p.n_chunks = 1;
+            p.blocks_per_tile = kNarrowTile / t_blk;
+            p.total_chunks = ceil_div(num_blocks, p.blocks_per_tile);
+        }
+        // only a block cut into several tiles can have a segment across a tile border
+        p.partials = p.n_chunks > 1;
     }
     if (p.partials) {
         size_t off = 0;
@@ -867,7 +1005,8 @@ extern "C" bload_status bload_segment_reduce(const void* d_packed, const int32_t
     a.feat_dim = (int32_t)feat_dim;
     a.n_seq = (int32_t)n_seq;
     a.mean = op == BLOAD_MEAN ? 1 : 0;
-    a.inv_t_blk = 1.0 / (double)t_blk;
+    a.blocks_per_tile = p.blocks_per_tile;
+    a.magic_t_blk = (uint32_t)std::min<uint64_t>((((uint64_t)1 << 32) + (uint64_t)t_blk - 1) / (uint64_t)t_blk, 0xFFFFFFFFull);
     a.out = d_out;
     a.chunk = p.chunk;
     a.n_chunks = p.n_chunks;

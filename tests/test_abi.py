@@ -61,9 +61,9 @@ def test_workspace_queries(lib):
     f = lib.bload_segment_reduce_workspace_bytes
     f.restype = ctypes.c_size_t
     f.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int64, ctypes.c_int]
-    tiles = -(-324084 * 4000 // 4096)              # token segments can cross the 4096-slot tiles:
-    assert f(324084, 4000, 1, 3) == tiles * 16 + 2 * (-(-tiles * 8 // 16) * 16)   # a descriptor and two int64 partials each
-    assert f(324084, 4096, 1, 3) == 0 and f(5, 2048, 1, 3) == 0    # tiles that are whole blocks cut nothing
+    tiles = 324084 * 2                             # blocks of 5000 token slots are cut into two tiles each:
+    assert f(324084, 5000, 1, 3) == tiles * 16 + 2 * (-(-tiles * 8 // 16) * 16)   # a descriptor and two int64 partials per tile
+    assert f(324084, 4096, 1, 3) == 0 and f(5, 2048, 1, 3) == 0 and f(9, 33, 1, 3) == 0   # tiles of whole blocks cut nothing
     assert f(34576, 3000, 80, 2) == 0              # one chunk per block
     assert f(180, 600, 37632, 0) == 0              # enough blocks x lane-slices: one chunk per block
     assert f(79, 3000, 2048, 1) > 0                # few blocks: cut in time, partial sums needed
