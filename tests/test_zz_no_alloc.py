@@ -24,9 +24,10 @@ def pack_both_ways(bl, n, T, F, kind, seed):
     got = bl.alloc_packed(plan.num_blocks, T, F, src.device)
     for t in (got.packed, got.seq_id, got.frame_idx, got.reset, got.valid):
         t.fill_(0x5A if t.dtype == torch.uint8 else 0x5A5A5A5A)      # garbage the call must overwrite
-    before = torch.cuda.memory_allocated()
+    count = lambda: torch.cuda.memory_stats()["allocation.all.allocated"]   # allocations made so far
+    before = count()
     bl.bload_pack_noalloc(src, d_so, d_L, plan, F, got)
-    assert torch.cuda.memory_allocated() == before                     # nothing came from torch either
+    assert count() == before                                           # nothing came from torch either
     torch.cuda.synchronize()
     for name in ("packed", "seq_id", "frame_idx", "reset", "valid"):
         assert torch.equal(getattr(got, name), getattr(want, name)), f"{name} differs (n={n} T={T} F={F})"
