@@ -6,9 +6,12 @@
 // every earlier draw.  So the chain itself runs on ONE wavefront and is kept as short
 // as the hardware allows, and everything around it is parallel:
 //   rf_order_kernel    seeded position p -> sequence, its length, checks, frame total
-//   rf_classes_kernel  L_dict: where each length's list starts, the lists themselves in
-//                      seeded order, and the running counts the chain starts from
-//                      (one workgroup, LDS)
+//   rf_count_kernel, rf_offsets_kernel, rf_scatter_kernel
+//                      L_dict: where each length's list starts, the lists themselves in
+//                      seeded order, and the running counts the chain starts from; the
+//                      seeded positions are cut into chunks, one workgroup each, that
+//                      count their lengths, learn where their part of every list
+//                      begins, and fill it in order
 //   rf_draw_kernel     the chain: per placement only (length, rank in its list, block,
 //                      offset) - no global load on the chain
 //   rf_assign_kernel   placement p -> sequence, and the per-sequence tables
@@ -19,6 +22,8 @@
 // steps; taking a sequence out lowers the sums behind it.
 #include "bload_common.hpp"
 #include "bload_order.hpp"
+
+#include <algorithm>
 
 namespace bload {
 
@@ -70,23 +75,45 @@ __global__ __launch_bounds__(kThreads) void rf_order_kernel(
 // the r-th sequence of that length in seeded order.  For the chain: within[g * 65 + j] =
 // sequences of the lengths g*64+1 .. g*64+j (j = 0..64, lengths taken in groups of 64) and
 // group_before[g] = sequences shorter than group g's lengths (the total for g past the end).
-// One workgroup: the lists must come out in seeded order, so positions are taken tile
-// by tile, each thread ranking its sequence among the equal lengths before it in the tile.
-__global__ __launch_bounds__(kThreads) void rf_classes_kernel(
-    const int32_t* __restrict__ seeded, const int32_t* __restrict__ seeded_len, int32_t n_seq,
-    int32_t t_blk, int32_t* __restrict__ first, int32_t* __restrict__ within,
-    int32_t* __restrict__ group_before, int32_t* __restrict__ entry)
+//
+// The lists must come out in seeded order.  The seeded positions are cut into chunks of
+// `per_chunk` consecutive positions (a multiple of 256).  Step 1, one workgroup per chunk:
+// how many sequences of each length the chunk holds.
+constexpr int kRfMaxChunks = 128;
+
+__global__ __launch_bounds__(kThreads) void rf_count_kernel(const int32_t* __restrict__ seeded_len,
+                                                            int32_t n_seq, int32_t t_blk, int32_t per_chunk,
+                                                            int32_t* __restrict__ chunk_count)
 {
     __shared__ int32_t s_fill[kRfMaxT];
-    __shared__ int32_t s_key[kThreads];
+    const int tid = (int)threadIdx.x;
+    const int lengths_kept = ((t_blk + kWave - 1) / kWave) * kWave;
+    for (int e = tid; e < lengths_kept; e += kThreads) s_fill[e] = 0;
+    __syncthreads();
+    const int64_t lo = (int64_t)blockIdx.x * per_chunk;
+    const int64_t hi = min((int64_t)n_seq, lo + per_chunk);
+    for (int64_t p = lo + tid; p < hi; p += kThreads) {
+        const int32_t len = seeded_len[p];
+        if (len) atomicAdd(&s_fill[len - 1], 1);
+    }
+    __syncthreads();
+    for (int e = tid; e < lengths_kept; e += kThreads) chunk_count[(int64_t)blockIdx.x * kRfMaxT + e] = s_fill[e];
+}
+
+// Step 2, one workgroup: the totals per length, from them first[], within[] and group_before[],
+// and in place of every chunk's counts the place where its part of each list begins.
+__global__ __launch_bounds__(kThreads) void rf_offsets_kernel(
+    int32_t n_chunks, int32_t t_blk, int32_t* __restrict__ chunk_count, int32_t* __restrict__ first,
+    int32_t* __restrict__ within, int32_t* __restrict__ group_before)
+{
+    __shared__ int32_t s_fill[kRfMaxT];
     __shared__ int32_t s_scan[kThreads];
     const int tid = (int)threadIdx.x;
     const int groups = (t_blk + kWave - 1) / kWave;
-    for (int e = tid; e < groups * kWave; e += kThreads) s_fill[e] = 0;
-    __syncthreads();
-    for (int32_t p = tid; p < n_seq; p += kThreads) {
-        const int32_t len = seeded_len[p];
-        if (len) atomicAdd(&s_fill[len - 1], 1);
+    for (int e = tid; e < groups * kWave; e += kThreads) {
+        int32_t total = 0;
+        for (int c = 0; c < n_chunks; ++c) total += chunk_count[(int64_t)c * kRfMaxT + e];
+        s_fill[e] = total;
     }
     __syncthreads();
 
@@ -110,15 +137,41 @@ __global__ __launch_bounds__(kThreads) void rf_classes_kernel(
             const int e = tid * kWave + j;
             const int32_t c = s_fill[e];
             if (e < t_blk) first[e] = run;
-            s_fill[e] = run;                // from here on: next free place of the list
+            s_fill[e] = run;                // start of the list of length e + 1
             run += c;
         }
     }
     __syncthreads();
+    // a chunk's part of a list begins behind the parts of the chunks before it
+    for (int e = tid; e < groups * kWave; e += kThreads) {
+        int32_t at = s_fill[e];
+        for (int c = 0; c < n_chunks; ++c) {
+            const int64_t k = (int64_t)c * kRfMaxT + e;
+            const int32_t count = chunk_count[k];
+            chunk_count[k] = at;
+            at += count;
+        }
+    }
+}
 
-    for (int32_t tile = 0; tile < n_seq; tile += kThreads) {
-        const int32_t p = tile + tid;
-        const int32_t len = p < n_seq ? seeded_len[p] : 0;
+// Step 3, one workgroup per chunk: its sequences into their lists, in seeded order: tile by
+// tile of 256 positions, each thread ranking its sequence among the equal lengths before it
+// in the tile.
+__global__ __launch_bounds__(kThreads) void rf_scatter_kernel(
+    const int32_t* __restrict__ seeded, const int32_t* __restrict__ seeded_len, int32_t n_seq,
+    int32_t t_blk, int32_t per_chunk, const int32_t* __restrict__ chunk_start, int32_t* __restrict__ entry)
+{
+    __shared__ int32_t s_fill[kRfMaxT];         // next free place of every list, for this chunk
+    __shared__ int32_t s_key[kThreads];
+    const int tid = (int)threadIdx.x;
+    const int lengths_kept = ((t_blk + kWave - 1) / kWave) * kWave;
+    for (int e = tid; e < lengths_kept; e += kThreads) s_fill[e] = chunk_start[(int64_t)blockIdx.x * kRfMaxT + e];
+    __syncthreads();
+    const int64_t lo = (int64_t)blockIdx.x * per_chunk;
+    const int64_t hi = min((int64_t)n_seq, lo + per_chunk);
+    for (int64_t tile = lo; tile < hi; tile += kThreads) {
+        const int64_t p = tile + tid;
+        const int32_t len = p < hi ? seeded_len[p] : 0;
         s_key[tid] = len;
         __syncthreads();
         int32_t rank = 0;
@@ -246,7 +299,8 @@ __global__ __launch_bounds__(kThreads) void rf_assign_kernel(
 }
 
 struct RfLayout {
-    size_t result, seeded, seeded_len, entry, pick, first, within, group_before, bytes;
+    size_t result, seeded, seeded_len, entry, pick, first, within, group_before, chunk_count, bytes;
+    int32_t n_chunks, per_chunk;
 };
 
 static RfLayout rf_layout(int64_t n_seq)
@@ -263,6 +317,12 @@ static RfLayout rf_layout(int64_t n_seq)
     l.first = take((size_t)kRfMaxT * 4);
     l.within = take((size_t)kRfGroups * kRfStride * 4);
     l.group_before = take((size_t)kRfGroups * 4);
+    // chunks of whole 256-position tiles, at most kRfMaxChunks of them, at least 4 tiles each
+    const int64_t tiles = ceil_div((int64_t)n, kThreads);
+    const int64_t tiles_per_chunk = std::max<int64_t>(4, ceil_div(tiles, kRfMaxChunks));
+    l.per_chunk = (int32_t)(tiles_per_chunk * kThreads);
+    l.n_chunks = (int32_t)std::max<int64_t>(1, ceil_div((int64_t)n, l.per_chunk));
+    l.chunk_count = take((size_t)l.n_chunks * kRfMaxT * 4);
     l.bytes = off;
     return l;
 }
@@ -309,6 +369,7 @@ extern "C" bload_status bload_plan_random_fit(const int32_t* d_lengths, int64_t 
     int32_t* first = reinterpret_cast<int32_t*>(ws + l.first);
     int32_t* within = reinterpret_cast<int32_t*>(ws + l.within);
     int32_t* group_before = reinterpret_cast<int32_t*>(ws + l.group_before);
+    int32_t* chunk_count = reinterpret_cast<int32_t*>(ws + l.chunk_count);
 
     const int32_t n = (int32_t)n_seq;
     const OrderKey key = make_order_key(n_seq, seed);
@@ -318,8 +379,12 @@ extern "C" bload_status bload_plan_random_fit(const int32_t* d_lengths, int64_t 
     hipLaunchKernelGGL(rf_clear_kernel, dim3(1), dim3(1), 0, stream, result);
     hipLaunchKernelGGL(rf_order_kernel, per_item, block, 0, stream, d_lengths, n, t_blk, key, seeded,
                        seeded_len, result);
-    hipLaunchKernelGGL(rf_classes_kernel, dim3(1), block, 0, stream, seeded, seeded_len, n, t_blk,
-                       first, within, group_before, entry);
+    hipLaunchKernelGGL(rf_count_kernel, dim3((uint32_t)l.n_chunks), block, 0, stream, seeded_len, n, t_blk,
+                       l.per_chunk, chunk_count);
+    hipLaunchKernelGGL(rf_offsets_kernel, dim3(1), block, 0, stream, l.n_chunks, t_blk, chunk_count, first,
+                       within, group_before);
+    hipLaunchKernelGGL(rf_scatter_kernel, dim3((uint32_t)l.n_chunks), block, 0, stream, seeded, seeded_len,
+                       n, t_blk, l.per_chunk, chunk_count, entry);
     // after a length outside [1, t_blk] the last two kernels return at once
     if (t_blk > kWave * kWave)
         hipLaunchKernelGGL(rf_draw_kernel<true>, dim3(1), dim3(kWave), 0, stream, within, group_before,
