@@ -233,6 +233,36 @@ def run_workload(args, wid: int, cold_sets: int = 0) -> dict:
     return out
 
 
+def yardsticks() -> dict:
+    """What plain library kernels reach on this GPU in this run, as same-run references for the
+    roofline fractions: an elementwise copy (1 GiB read + 1 GiB written) and a fill (1 GiB
+    written), both torch's own kernels, timed with events."""
+    import torch
+
+    dev = torch.device("cuda:0")
+    a = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+    b = torch.empty_like(a)
+    gib = float(1 << 30)
+
+    def gbps(fn, nbytes):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return nbytes * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    out = {"copy_GBps": gbps(lambda: torch.mul(a, 1.0, out=b), 2 * gib),
+           "fill_GBps": gbps(lambda: b.fill_(0.0), gib),
+           "what": "torch elementwise copy (1 GiB read + 1 GiB written) and fill (1 GiB written)"}
+    del a, b
+    torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(args, wid: int, budget_frames: int) -> dict:
     """The oracle as it stands, one thread: order + plan + pack + reduce of the first sequences
     of the workload (as many as hold about `budget_frames` frames), with the workload's T_blk."""
@@ -347,9 +377,12 @@ def main() -> int:
                                  "segment_reduce_frac": r["segment_reduce"]["frac"]}
         result["per_workload"] = per
 
+    if not args.only:
+        result["yardsticks"] = yardsticks()
     if not args.no_cpu_baseline and args.world == 1:
-        # about 10-20 s of oracle time whatever the workload: ~8 M frame-copies of workload 4
-        budget = {1: 1 << 40, 2: 1 << 40, 3: 1 << 40, 4: 8_000_000, 5: 400_000_000}[args.workload]
+        # a few seconds of oracle time on the GPU machine's host (the whole workload, or half of workload 4,
+        # whose 58 GB of source and packed tensor need not be held twice)
+        budget = {1: 1 << 40, 2: 1 << 40, 3: 1 << 40, 4: 40_000_000, 5: 1 << 40}[args.workload]
         result["cpu_baseline"] = cpu_baseline(args, args.workload, budget)
     print(json.dumps(result))
     return 0

@@ -162,16 +162,31 @@ struct ScanLane {
     {
         const int64_t frame_bytes = (int64_t)a.feat_dim * (int64_t)sizeof(ElemT);
         const uint8_t* src = frames + first_elem * (int64_t)sizeof(ElemT);
+        // A batch of nothing but padding (block tails) must not cost HBM reads.  With one or two
+        // loads per slot it is skipped by a branch (measured on 320-byte float frames: 13.9 ->
+        // 10.4 ms); with four (byte payloads) the branch costs more than it saves in blocks that
+        // are mostly full, so there the loads stay unconditional and re-read the block's first
+        // frame, which sits in the cache.
+        const bool wanted = f.valid != 0;
+        constexpr bool kSkipByBranch = QUADS <= 2;
         if (VEC) {
             ScanQuad<ElemT> x[kScanBatch][QUADS];
+            if (!kSkipByBranch || wanted) {
 #pragma unroll
-            for (int u = 0; u < kScanBatch; ++u) {
-                const uint8_t* frame = src + (int64_t)min(t + u, a.t_blk - 1) * frame_bytes;
+                for (int u = 0; u < kScanBatch; ++u) {
+                    const uint8_t* frame = src + (int64_t)(wanted ? min(t + u, a.t_blk - 1) : 0) * frame_bytes;
 #pragma unroll
-                for (int g = 0; g < QUADS; ++g) {
-                    const int64_t at = quad_on[g] ? (int64_t)g * quad_stride * (int64_t)sizeof(ElemT) : 0;
-                    x[u][g].bits = __builtin_nontemporal_load(
-                        reinterpret_cast<const typename ScanBits<sizeof(ElemT) * 4>::T*>(frame + at));
+                    for (int g = 0; g < QUADS; ++g) {
+                        const int64_t at = quad_on[g] ? (int64_t)g * quad_stride * (int64_t)sizeof(ElemT) : 0;
+                        x[u][g].bits = __builtin_nontemporal_load(
+                            reinterpret_cast<const typename ScanBits<sizeof(ElemT) * 4>::T*>(frame + at));
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < kScanBatch; ++u) {
+#pragma unroll
+                    for (int g = 0; g < QUADS; ++g) x[u][g].bits = typename ScanBits<sizeof(ElemT) * 4>::T{};
                 }
             }
 #pragma unroll
@@ -193,7 +208,7 @@ struct ScanLane {
             ElemT x[kScanBatch];
 #pragma unroll
             for (int u = 0; u < kScanBatch; ++u)
-                x[u] = *reinterpret_cast<const ElemT*>(src + (int64_t)min(t + u, a.t_blk - 1) * frame_bytes);
+                x[u] = *reinterpret_cast<const ElemT*>(src + (int64_t)(wanted ? min(t + u, a.t_blk - 1) : 0) * frame_bytes);
 #pragma unroll
             for (int u = 0; u < kScanBatch; ++u) {
                 const bool is_valid = (f.valid >> u) & 1u, starts = (f.boundary >> u) & 1u;
