@@ -494,9 +494,46 @@ struct LaneFlags {
     bool tail_open;        // the tile's last slot is here and its segment goes on into the next tile
 };
 
-// Reads the flags of the lane's slots and of its neighbours and derives the masks.  Called by
-// every thread of the workgroup (the lanes of a wave exchange their border slots).
-__device__ __forceinline__ LaneFlags narrow_lane_flags(const ReduceArgs& a, const NarrowTile& tile)
+// The flag bytes of a lane as they come from memory, and what the whole wave is, as far as a
+// look at whole words can tell.
+struct LaneFlagBytes {
+    vec16 valid, reset;    // zero where the lane has not all its 16 slots in the tile
+    bool wave_blank;       // the wave holds nothing but padding
+    bool wave_plain;       // the wave holds nothing but valid slots without a start flag
+};
+
+__device__ __forceinline__ LaneFlagBytes narrow_flag_bytes(const ReduceArgs& a, const NarrowTile& tile)
+{
+    constexpr int SPL = kSlotsPerLane;
+    static_assert(SPL == 16, "the flags of a lane are one 16-byte vector per plane");
+    const int pos0 = (int)threadIdx.x * SPL;
+    const int32_t left = tile.n - pos0;
+    LaneFlagBytes b;
+    b.valid = vec16{0u, 0u, 0u, 0u};
+    b.reset = vec16{0u, 0u, 0u, 0u};
+    if (left >= SPL) {
+        b.valid = __builtin_nontemporal_load(reinterpret_cast<const vec16_any*>(a.valid + tile.g0 + pos0));
+        b.reset = __builtin_nontemporal_load(reinterpret_cast<const vec16_any*>(a.reset + tile.g0 + pos0));
+    }
+    // Two kinds of waves are common in packed blocks and need no byte-by-byte look at their
+    // flags: nothing but padding (block tails), and nothing but valid slots without a start flag
+    // (the inside of long sequences).  Both tests are wave-uniform.
+    const uint32_t v_any = b.valid[0] | b.valid[1] | b.valid[2] | b.valid[3];
+    const uint32_t v_all = b.valid[0] & b.valid[1] & b.valid[2] & b.valid[3];
+    const uint32_t r_any = b.reset[0] | b.reset[1] | b.reset[2] | b.reset[3];
+    const bool lane_blank = left >= SPL ? v_any == 0u : left <= 0;
+    // (a non-zero byte in the AND of the four words means four non-zero bytes)
+    const bool lane_plain = left >= SPL && r_any == 0u &&
+                            ((((v_all & 0x7f7f7f7fu) + 0x7f7f7f7fu) | v_all) & 0x80808080u) == 0x80808080u;
+    b.wave_blank = __ballot(lane_blank) == ~0ull;
+    b.wave_plain = __ballot(lane_plain) == ~0ull;
+    return b;
+}
+
+// Derives the masks of the lane's slots from its flag bytes and those of its neighbours.
+// Called by every thread of the workgroup (the lanes of a wave exchange their border slots).
+__device__ __forceinline__ LaneFlags narrow_lane_flags(const ReduceArgs& a, const NarrowTile& tile,
+                                                       const LaneFlagBytes& bytes)
 {
     constexpr int SPL = kSlotsPerLane;
     constexpr uint32_t ALL = (1u << SPL) - 1u;
@@ -522,30 +559,14 @@ __device__ __forceinline__ LaneFlags narrow_lane_flags(const ReduceArgs& a, cons
     if (lane == 0 && rem0 != 0 && left > 0) before_valid = a.valid[s0 - 1];
     if (lane == kWave - 1 && rem_next != 0 && left >= SPL) { after_valid = a.valid[s0 + SPL]; after_reset = a.reset[s0 + SPL]; }
 
-    static_assert(SPL == 16, "the flags of a lane are one 16-byte vector per plane");
-    const bool whole = left >= SPL;                      // all 16 slots lie in the tile
-    vec16 uv = {0u, 0u, 0u, 0u}, ur = {0u, 0u, 0u, 0u};
-    if (whole) {
-        uv = __builtin_nontemporal_load(reinterpret_cast<const vec16_any*>(a.valid + s0));
-        ur = __builtin_nontemporal_load(reinterpret_cast<const vec16_any*>(a.reset + s0));
-    }
-    // Two kinds of waves are common in packed blocks and need no byte-by-byte look at their
-    // flags: nothing but padding (block tails), and nothing but valid slots without a start flag
-    // (the inside of long sequences).  Both tests are wave-uniform.
-    const uint32_t v_any = uv[0] | uv[1] | uv[2] | uv[3], v_all = uv[0] & uv[1] & uv[2] & uv[3];
-    const uint32_t r_any = ur[0] | ur[1] | ur[2] | ur[3];
-    const bool lane_blank = whole ? v_any == 0u : left <= 0;
-    // (a non-zero byte in the AND of the four words means four non-zero bytes)
-    const bool lane_plain = whole && r_any == 0u &&
-                            ((((v_all & 0x7f7f7f7fu) + 0x7f7f7f7fu) | v_all) & 0x80808080u) == 0x80808080u;
     uint32_t vmask = 0, rmask = 0;
-    if (__ballot(lane_blank) == ~0ull) {
+    if (bytes.wave_blank) {
         // vmask = rmask = 0
-    } else if (__ballot(lane_plain) == ~0ull) {
+    } else if (bytes.wave_plain) {
         vmask = ALL;
-    } else if (whole) {
-        vmask = nonzero_bytes16(uv);
-        rmask = nonzero_bytes16(ur);
+    } else if (left >= SPL) {
+        vmask = nonzero_bytes16(bytes.valid);
+        rmask = nonzero_bytes16(bytes.reset);
     } else if (left > 0) {
         // the tile ends inside this lane: slot by slot (those past the end re-read its last slot)
 #pragma unroll
@@ -590,41 +611,54 @@ struct NarrowStage {
     static constexpr int kVectors = NV > 1 ? kThreads * kStride : 1;
 };
 
-// The lane's 16 elements of feature d; only those of valid slots mean anything.  ONE: a frame
-// is one element, so a wave's 1024 elements are contiguous: they are read as whole 1 KiB rows
-// (lane l takes vector l of each row) and handed to their lanes through LDS, because 64 lanes
-// that each read their own 64 bytes would touch four times as many cache lines per load.
-// Otherwise one load per slot, all issued together.  `left` = slots from the lane's first one
-// to the tile's end; `stage` = the workgroup's staging area (ONE only).
-template <typename ElemT, bool ONE>
-__device__ __forceinline__ void narrow_load(const ReduceArgs& a, int64_t s0, int32_t left, int d,
-                                            vec16* stage, ElemT (&raw)[kSlotsPerLane])
-{
-    constexpr int SPL = kSlotsPerLane;
-    constexpr int NV = NarrowStage<ElemT>::NV;
-    const int lane = lane_id();
-    // does the whole wave lie inside the tile (its last lane has all its slots)
-    const bool wave_whole = left - (kWave - 1 - lane) * SPL >= SPL;
-    if (ONE && NV > 1 && wave_whole) {
-        union { vec16 v[NV]; ElemT e[SPL]; } u;
-        const vec16_any* row = reinterpret_cast<const vec16_any*>(a.packed + (s0 - lane * SPL) * (int64_t)sizeof(ElemT));
+// The payload of a wave whose 1024 elements are contiguous (a frame is one element, every lane
+// has all its slots): read as whole 1 KiB rows, lane l taking vector l of each row, because 64
+// lanes that each read their own 64 bytes would touch four times as many cache lines per load.
+// `issue` only starts the loads (so that the work on the flags runs while they are in flight),
+// `finish` hands every vector to the lane it belongs to, through LDS.
+template <typename ElemT>
+struct NarrowRows {
+    static constexpr int NV = NarrowStage<ElemT>::NV;
+    vec16 v[NV > 0 ? NV : 1];
+
+    __device__ __forceinline__ void issue(const ReduceArgs& a, int64_t wave_s0)
+    {
+        const vec16_any* row = reinterpret_cast<const vec16_any*>(a.packed + wave_s0 * (int64_t)sizeof(ElemT));
+#pragma unroll
+        for (int k = 0; k < NV; ++k) v[k] = __builtin_nontemporal_load(row + k * kWave + lane_id());
+    }
+    __device__ __forceinline__ void finish(vec16* stage, ElemT (&raw)[kSlotsPerLane])
+    {
+        const int lane = lane_id();
         vec16* mine = stage + (int)(threadIdx.x - lane) * NarrowStage<ElemT>::kStride;     // the wave's part
 #pragma unroll
-        for (int k = 0; k < NV; ++k) u.v[k] = __builtin_nontemporal_load(row + k * kWave + lane);
-#pragma unroll
         for (int k = 0; k < NV; ++k) {
-            const int v = k * kWave + lane;                  // vector v of the wave belongs to lane v / NV
-            mine[(v / NV) * NarrowStage<ElemT>::kStride + (v % NV)] = u.v[k];
+            const int at = k * kWave + lane;                 // vector `at` of the wave belongs to lane at / NV
+            mine[(at / NV) * NarrowStage<ElemT>::kStride + (at % NV)] = v[k];
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        union { vec16 q[NV > 0 ? NV : 1]; ElemT e[kSlotsPerLane]; } u;
 #pragma unroll
-        for (int k = 0; k < NV; ++k) u.v[k] = mine[lane * NarrowStage<ElemT>::kStride + k];
+        for (int k = 0; k < NV; ++k) u.q[k] = mine[lane * NarrowStage<ElemT>::kStride + k];
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int j = 0; j < SPL; ++j) raw[j] = u.e[j];
-    } else if (ONE && left >= SPL) {
+        for (int j = 0; j < kSlotsPerLane; ++j) raw[j] = u.e[j];
+    }
+};
+
+// The lane's 16 elements of feature d where they do not come as rows; only those of valid slots
+// mean anything.  ONE: a frame is one element, so they are contiguous and come as 16-byte
+// vectors.  Otherwise one load per slot, all issued together.  `left` = slots from the lane's
+// first one to the tile's end.
+template <typename ElemT, bool ONE>
+__device__ __forceinline__ void narrow_load(const ReduceArgs& a, int64_t s0, int32_t left, int d,
+                                            ElemT (&raw)[kSlotsPerLane])
+{
+    constexpr int SPL = kSlotsPerLane;
+    constexpr int NV = NarrowStage<ElemT>::NV;
+    if (ONE && left >= SPL) {
         union { vec16 v[NV > 0 ? NV : 1]; ElemT e[SPL]; } u;
         const vec16_any* from = reinterpret_cast<const vec16_any*>(a.packed + s0 * (int64_t)sizeof(ElemT));
 #pragma unroll
@@ -705,45 +739,58 @@ __global__ __launch_bounds__(kThreads) void reduce_narrow_kernel(ReduceArgs a)
     const int pos0 = tid * SPL;
     const int64_t s0 = g0 + pos0;
     if (tid == 0) s_desc = ChunkDesc{kHeadNone, 0, 0, -1};
-    const LaneFlags f = narrow_lane_flags(a, tile);
+    const LaneFlagBytes bytes = narrow_flag_bytes(a, tile);
+    // a wave without a valid slot reads no payload; a wave that lies whole in the tile asks for
+    // its rows now, before the flags are looked at
+    const bool wave_valid = !bytes.wave_blank;
+    const int32_t left = tile.n - pos0;
+    const bool by_rows = ONE && NarrowStage<ElemT>::NV > 1 && left - (kWave - 1 - lane) * SPL >= SPL;
+    NarrowRows<ElemT> rows;
+    if (wave_valid && by_rows) rows.issue(a, s0 - lane * SPL);
+    const LaneFlags f = narrow_lane_flags(a, tile, bytes);
     const uint32_t bmask = f.bmask;
     const unsigned long long wave_breaks = __ballot(bmask != 0);
-    const bool wave_valid = __ballot(f.vmask != 0) != 0;     // a wave without a valid slot reads no payload
     const int last_break = bmask ? 31 - __clz((int)bmask) : 0;
+    const int first_break = bmask ? __ffs((int)bmask) - 1 : SPL;
     // the sequence that starts at the lane's last break: asked for now, so that the answer is
     // there when a lane further on (or this one) closes that segment
     int32_t own_seq = -1;
     if (bmask && ((f.vmask >> last_break) & 1u)) own_seq = a.seq_id[s0 + last_break];
     if (lane == 0) s_wave_breaks[wave] = wave_breaks;
     const uint32_t from_last_break = f.vmask & (~0u << last_break);   // the lane's part of the open segment
+    const uint32_t to_first_break = f.vmask & ((1u << first_break) - 1u);   // its part of the segment it inherits
     const bool finishes = f.ends != 0 || f.tail_open;                 // a piece ends in this lane
     int32_t prev_start = -1;           // position of the last break in front of this lane, -1: none in the tile
     int32_t prev_seq = -1;             // and the sequence id found there
 
     const int n_feat = ONE ? 1 : a.feat_dim;
     for (int d = 0; d < n_feat; ++d) {
-        ElemT raw[SPL];
         SegState<Acc> scan, carry;
         Acc tail = 0;                  // the lane's slots from its last break on (all of them if it has none)
+        Acc head = 0;                  // the lane's slots in front of its first break
         if (!wave_valid) {
             // nothing but padding: every slot is a break, nothing to add
-#pragma unroll
-            for (int j = 0; j < SPL; ++j) raw[j] = ElemT{};
             scan = SegState<Acc>{0, 1u};
             carry = SegState<Acc>{0, lane == 0 ? 0u : 1u};
-        } else if (wave_breaks == 0) {
-            // no break in the whole wave (so every slot is valid): plain sums
-            narrow_load<ElemT, ONE>(a, s0, tile.n - pos0, d, s_stage, raw);
-#pragma unroll
-            for (int j = 0; j < SPL; ++j) tail += Elem<ElemT>::get(raw[j]);
-            scan = SegState<Acc>{wave_scan(tail, PlainSum<Acc>(), PlainMove<Acc>()), 0u};
-            carry = SegState<Acc>{dpp_move<kDppWaveShr1>(scan.sum, (Acc)0), 0u};
         } else {
-            narrow_load<ElemT, ONE>(a, s0, tile.n - pos0, d, s_stage, raw);
+            ElemT raw[SPL];
+            if (by_rows) rows.finish(s_stage, raw);
+            else narrow_load<ElemT, ONE>(a, s0, left, d, raw);
+            if (wave_breaks == 0) {
+                // no break in the whole wave (so every slot is valid): plain sums
 #pragma unroll
-            for (int j = 0; j < SPL; ++j) tail += masked((Acc)Elem<ElemT>::get(raw[j]), from_last_break, j);
-            scan = wave_scan(SegState<Acc>{tail, bmask != 0 ? 1u : 0u}, SegCombine<Acc>(), SegMove<Acc>());
-            carry = SegMove<Acc>().template at<kDppWaveShr1, 0xF>(scan);      // the lanes before this one
+                for (int j = 0; j < SPL; ++j) tail += Elem<ElemT>::get(raw[j]);
+                scan = SegState<Acc>{wave_scan(tail, PlainSum<Acc>(), PlainMove<Acc>()), 0u};
+                carry = SegState<Acc>{dpp_move<kDppWaveShr1>(scan.sum, (Acc)0), 0u};
+            } else {
+#pragma unroll
+                for (int j = 0; j < SPL; ++j) {
+                    tail += masked((Acc)Elem<ElemT>::get(raw[j]), from_last_break, j);
+                    head += masked((Acc)Elem<ElemT>::get(raw[j]), to_first_break, j);
+                }
+                scan = wave_scan(SegState<Acc>{tail, bmask != 0 ? 1u : 0u}, SegCombine<Acc>(), SegMove<Acc>());
+                carry = SegMove<Acc>().template at<kDppWaveShr1, 0xF>(scan);      // the lanes before this one
+            }
         }
         if (d > 0) __syncthreads();                  // the previous feature's wave sums are consumed
         if (lane == kWave - 1) { s_wave_sum[wave] = scan.sum; s_wave_any[wave] = scan.any; }
@@ -765,21 +812,26 @@ __global__ __launch_bounds__(kThreads) void reduce_narrow_kernel(ReduceArgs a)
             }
             if (holder >= 0) { prev_start = s_last_break[holder]; prev_seq = s_break_seq[holder]; }
         }
-        // one piece per end (usually one per lane): the slots from the last break at or before the
-        // end -- or from the lane's first slot, behind the carried sum, if there is none -- up to it
+        // One piece per end (usually one per lane).  The piece that closes what the lanes before
+        // left open ends in front of the lane's first break: carry + head.  The piece that the
+        // lane's last break opened ends at its last slot: tail (plus the carry if the lane has no
+        // break at all).  A piece between two breaks of the lane is read again, slot by slot.
         uint32_t todo = f.ends | (f.tail_open ? 1u << f.j_last : 0u);
         while (todo) {
             const int j = 31 - __clz((int)todo);                          // last one first
             todo &= ~(1u << j);
             const uint32_t upto = bmask & ((2u << j) - 1u);               // breaks at or before j
             const int lb = upto ? 31 - __clz((int)upto) : -1;
-            Acc sum = lb >= 0 ? (Acc)0 : carry.sum;
-            if (j == SPL - 1) {
-                sum += tail;        // the lane's last slot closes what its last break (or the carry) opened
+            Acc sum;
+            if (lb < 0) {
+                sum = carry.sum + (bmask ? head : tail);
+            } else if (lb == last_break) {
+                sum = tail;
             } else {
-                const uint32_t piece = f.vmask & ((2u << j) - 1u) & (lb >= 0 ? ~0u << lb : ~0u);
-#pragma unroll
-                for (int k = 0; k < SPL; ++k) sum += masked((Acc)Elem<ElemT>::get(raw[k]), piece, k);
+                sum = 0;
+                const int64_t stride = (int64_t)(ONE ? 1 : a.feat_dim) * (int64_t)sizeof(ElemT);
+                const uint8_t* from = a.packed + ((s0 + lb) * (ONE ? 1 : a.feat_dim) + d) * (int64_t)sizeof(ElemT);
+                for (int k = lb; k <= j; ++k, from += stride) sum += Elem<ElemT>::get(*reinterpret_cast<const ElemT*>(from));
             }
             const int32_t start = lb >= 0 ? pos0 + lb : prev_start;
             const int32_t cnt = start >= 0 ? pos0 + j - start + 1 : pos0 + j + 1;
