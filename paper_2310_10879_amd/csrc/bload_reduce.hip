@@ -602,13 +602,17 @@ __device__ __forceinline__ LaneFlags narrow_lane_flags(const ReduceArgs& a, cons
     return r;
 }
 
-// LDS staging of the payload of one workgroup: the 16-byte vectors of a lane, one spare vector
-// apart so that neighbouring lanes start in different banks.
+// LDS staging of the payload of one workgroup: the NV 16-byte vectors of a lane lie together,
+// vector k of lane l in place k ^ (l / (16 / NV)) of the lane's NV, so that the 16 lanes which
+// one pass of a 16-byte LDS access serves touch every bank once, both when a lane writes vector
+// l of a row and when it reads its own vectors.
 template <typename ElemT>
 struct NarrowStage {
     static constexpr int NV = kSlotsPerLane * (int)sizeof(ElemT) / 16;     // vectors per lane
-    static constexpr int kStride = NV + 1;
-    static constexpr int kVectors = NV > 1 ? kThreads * kStride : 1;
+    static_assert(NV == 1 || NV == 2 || NV == 4, "the bank swizzle below is written for 1, 2 or 4 vectors");
+    static constexpr int kVectors = NV > 1 ? kThreads * NV : 1;
+    // place of vector k of lane l (l counted within the wave) in the wave's part of the stage
+    __device__ static __forceinline__ int at(int l, int k) { return l * NV + (k ^ ((l / (16 / NV)) & (NV - 1))); }
 };
 
 // The payload of a wave whose 1024 elements are contiguous (a frame is one element, every lane
@@ -630,18 +634,18 @@ struct NarrowRows {
     __device__ __forceinline__ void finish(vec16* stage, ElemT (&raw)[kSlotsPerLane])
     {
         const int lane = lane_id();
-        vec16* mine = stage + (int)(threadIdx.x - lane) * NarrowStage<ElemT>::kStride;     // the wave's part
+        vec16* mine = stage + (int)(threadIdx.x - lane) * NV;                // the wave's part
 #pragma unroll
         for (int k = 0; k < NV; ++k) {
-            const int at = k * kWave + lane;                 // vector `at` of the wave belongs to lane at / NV
-            mine[(at / NV) * NarrowStage<ElemT>::kStride + (at % NV)] = v[k];
+            const int row_at = k * kWave + lane;             // vector `row_at` of the wave belongs to lane row_at / NV
+            mine[NarrowStage<ElemT>::at(row_at / NV, row_at % NV)] = v[k];
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         union { vec16 q[NV > 0 ? NV : 1]; ElemT e[kSlotsPerLane]; } u;
 #pragma unroll
-        for (int k = 0; k < NV; ++k) u.q[k] = mine[lane * NarrowStage<ElemT>::kStride + k];
+        for (int k = 0; k < NV; ++k) u.q[k] = mine[NarrowStage<ElemT>::at(lane, k)];
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int j = 0; j < kSlotsPerLane; ++j) raw[j] = u.e[j];
