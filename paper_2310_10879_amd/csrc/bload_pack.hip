@@ -209,6 +209,19 @@ __device__ __forceinline__ void write_range(uint8_t* packed, int64_t lo, int64_t
     }
 }
 
+// The start-table entry of one slot (frame index -1: padding).  Streamed like the payload: plain
+// stores leave these planes (a gigabyte at 10^8 slots) as modified lines in the memory-side
+// cache, and a consumer that streams the packed tensor right afterwards then reads about a tenth
+// slower (measured: the reduction of 3000 x 320-byte blocks takes 3.98 ms alone and 4.45 ms
+// behind a pack that wrote them with plain stores).
+__device__ __forceinline__ void store_slot(const PackArgs& a, int64_t slot, int32_t seq, int32_t fid)
+{
+    __builtin_nontemporal_store(seq, a.seq_id + slot);
+    __builtin_nontemporal_store(fid, a.frame_idx + slot);
+    __builtin_nontemporal_store((uint8_t)(fid == 0), a.reset + slot);
+    __builtin_nontemporal_store((uint8_t)(fid >= 0), a.valid + slot);
+}
+
 // Start-table entries of global slots [lo, hi): lane k of the calling wave writes the slots
 // lo + k, lo + k + 64, ...  frame0 = frame index of slot lo, or -1 for padding.
 __device__ __forceinline__ void write_slots(const PackArgs& a, int64_t lo, int64_t hi, int32_t seq,
@@ -217,10 +230,7 @@ __device__ __forceinline__ void write_slots(const PackArgs& a, int64_t lo, int64
     for (int64_t k = lane_id(); lo + k < hi; k += kWave) {
         const int64_t g = lo + k;
         const int32_t fid = frame0 < 0 ? -1 : (int32_t)(frame0 + k);
-        a.seq_id[g] = frame0 < 0 ? -1 : seq;
-        a.frame_idx[g] = fid;
-        a.reset[g] = (uint8_t)(fid == 0);
-        a.valid[g] = (uint8_t)(fid >= 0);
+        store_slot(a, g, frame0 < 0 ? -1 : seq, fid);
     }
 }
 
@@ -303,10 +313,7 @@ __global__ __launch_bounds__(kThreads) void pack_wide_kernel(
                     // frames t of this run with D0 <= run_lo + t * F < D1
                     for (int64_t t = floor_div(D0 - run_lo + F - 1, F, inv_frame_bytes) + lane_id();
                          run_lo + t * F < D1 && t < len; t += kWave) {
-                        a.seq_id[g + t] = r.seq;
-                        a.frame_idx[g + t] = (int32_t)t;
-                        a.reset[g + t] = (uint8_t)(t == 0);
-                        a.valid[g + t] = 1;
+                        store_slot(a, g + t, r.seq, (int32_t)t);
                     }
                 }
                 return;
@@ -318,10 +325,7 @@ __global__ __launch_bounds__(kThreads) void pack_wide_kernel(
                 if (table_wave) {
                     for (int64_t slot = floor_div(D0 + F - 1, F, inv_frame_bytes) + lane_id(); slot * F < D1;
                          slot += kWave) {
-                        a.seq_id[slot] = -1;
-                        a.frame_idx[slot] = -1;
-                        a.reset[slot] = 0;
-                        a.valid[slot] = 0;
+                        store_slot(a, slot, -1, -1);
                     }
                 }
                 return;
@@ -440,10 +444,7 @@ __global__ __launch_bounds__(kThreads) void pack_wide_kernel(
                 seq = s_run_seq[k];
                 fid = (int32_t)(slot - floor_div(s_run_lo[k], F, inv_frame_bytes));
             }
-            a.seq_id[slot] = seq;
-            a.frame_idx[slot] = fid;
-            a.reset[slot] = (uint8_t)(fid == 0);
-            a.valid[slot] = (uint8_t)(fid >= 0);
+            store_slot(a, slot, seq, fid);
         }
     }
 }
@@ -543,10 +544,7 @@ __global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a,
             __builtin_nontemporal_store(vl, reinterpret_cast<uint32_t*>(a.valid + g));
         } else {
             for (int j = 0; s0 + j < nslot; ++j) {
-                a.seq_id[g + j] = sid[j];
-                a.frame_idx[g + j] = fid[j];
-                a.reset[g + j] = (uint8_t)(fid[j] == 0);
-                a.valid[g + j] = (uint8_t)(fid[j] >= 0);
+                store_slot(a, g + j, sid[j], fid[j]);
             }
         }
     }

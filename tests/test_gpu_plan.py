@@ -13,7 +13,10 @@ pytestmark = pytest.mark.gpu
 @pytest.mark.parametrize("kind", ["uniform", "short", "long", "mixed"])
 @pytest.mark.parametrize("n,T", [(1, 1), (1, 9), (2, 2), (3, 5), (64, 32), (255, 7), (257, 600),
                                  (1000, 600), (2047, 33), (2048, 1), (2049, 4096), (5000, 3),
-                                 (70001, 100)])
+                                 (70001, 100),
+                                 # around the tiles of the scans (2048) and of the jumping (8192)
+                                 (4096, 17), (4097, 900), (8191, 2), (8192, 50), (8193, 7),
+                                 (16384, 64), (16385, 300), (24577, 5)])
 def test_plan_matches_oracle(kind, n, T):
     rng = np.random.default_rng(n * 7 + T)
     L = workloads.random_lengths(rng, n, T, kind)
