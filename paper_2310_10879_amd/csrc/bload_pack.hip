@@ -66,57 +66,47 @@ template <int MAXRUNS>
 struct RunTable {
     int64_t src[MAXRUNS];      // first source frame of the run
     int32_t dst[MAXRUNS + 1];  // first slot, tile relative; [n] = INT_MAX sentinel
-    int32_t len[MAXRUNS];      // frames in the run
+    int16_t end[MAXRUNS];      // one past its last slot, tile relative, cut to [0, MAXRUNS]: 18 bytes per
+                               // run keep the table of a 1024-slot tile under an eighth of a CU's LDS
     int32_t seq[MAXRUNS];      // original sequence index
-    int32_t n;
 };
 
-// Fill `tab` with the runs that can overlap global slots [gs_lo, gs_hi), reading
-// the run table forward from position `first` (the tile's entry of the
-// prepare pass: the last position of the tile's first block that starts at or
-// before gs_lo).  Called by the whole workgroup, one candidate position per
-// participating thread and step; runs are sorted by destination, so the runs to keep are a
-// prefix of the candidates and candidate k becomes table entry k.  Ends with
-// a barrier.
+// Fill `tab` with the runs that can overlap global slots [gs_lo, gs_hi): the shuffled positions
+// first .. last, where `first` is the tile's entry of the prepare pass (the last position of the
+// tile's first block that starts at or before gs_lo) and `last` that of the tile behind it (no
+// run that starts before gs_hi has a later position).  Runs are sorted by destination, so the
+// runs to keep are a prefix of these candidates; candidate k becomes table entry k, and a
+// candidate that starts at or behind gs_hi becomes an end mark (as does the entry behind the
+// last candidate), so that a search over all candidates finds only runs of the tile.  Called by
+// the whole workgroup, all look-ups in flight together; ends with a barrier.  Returns the
+// number of candidates.
 template <int MAXRUNS>
-__device__ __forceinline__ void gather_runs(const PackArgs& a, int32_t first, int64_t gs_lo,
-                                            int64_t gs_hi, RunTable<MAXRUNS>& tab)
+__device__ __forceinline__ int gather_runs(const Run* __restrict__ runs, int32_t n_seq, int32_t first,
+                                           int32_t last, int64_t gs_lo, int64_t gs_hi, RunTable<MAXRUNS>& tab)
 {
     const int tid = (int)threadIdx.x;
-    const int32_t n_seq = a.n_seq;
-    if (tid == 0) tab.n = INT_MAX;
-    __syncthreads();
-    // most tiles meet a handful of runs: look at 8 candidates first, then at 64,
-    // then at 256 per step, so that the table lookups stay in proportion
-    int32_t base = 0;
-    for (int32_t width = 8; base < MAXRUNS; base += width, width = width == 8 ? kWave : kThreads) {
-        const int32_t k = base + tid;
-        const int64_t q = (int64_t)first + k;
-        bool take = false;
-        if (tid < width && q < n_seq && k < MAXRUNS) {
-            const Run r = a.runs[q];
-            take = r.dst < gs_hi;
-            if (take) {
-                tab.src[k] = r.src;
-                tab.dst[k] = (int32_t)(r.dst - gs_lo);
-                tab.len[k] = r.len;
-                tab.seq[k] = r.seq;
-            }
+    const int n_cand = max(0, min(min(last, n_seq - 1) - first + 1, MAXRUNS));
+    constexpr int PER = (MAXRUNS + kThreads - 1) / kThreads;
+    Run r[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int k = tid + i * kThreads;
+        if (k < n_cand) r[i] = runs[(int64_t)first + k];
+    }
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int k = tid + i * kThreads;
+        if (k < n_cand) {
+            const bool take = r[i].dst < gs_hi;
+            tab.src[k] = r[i].src;
+            tab.dst[k] = take ? (int32_t)(r[i].dst - gs_lo) : INT_MAX;
+            tab.end[k] = (int16_t)min(max(r[i].dst - gs_lo + r[i].len, (int64_t)0), (int64_t)MAXRUNS);
+            tab.seq[k] = r[i].seq;
         }
-        // the first candidate that is not kept ends the table.  Whether any was refused comes
-        // out of the barrier itself (every wave sees the same answer, whatever a faster wave
-        // does to tab.n in its next step).
-        const bool refused = tid < width && !take;
-        const uint64_t refuse = __ballot(refused);
-        if (refuse && lane_id() == __ffsll((unsigned long long)refuse) - 1) atomicMin(&tab.n, k);
-        if (__syncthreads_or(refused ? 1 : 0)) break;
     }
-    if (tid == 0) {
-        const int32_t n = min(tab.n, MAXRUNS);
-        tab.n = n;
-        tab.dst[n] = INT_MAX;
-    }
+    if (tid == 0) tab.dst[n_cand] = INT_MAX;
     __syncthreads();
+    return n_cand;
 }
 
 // Index of the last run whose first slot is <= slot (tile relative), -1 if none.
@@ -460,7 +450,7 @@ template <int MAXRUNS>
 struct RunCursor {
     const RunTable<MAXRUNS>& tab;
     int r;
-    int32_t dst, len, next, seq;
+    int32_t dst, end, next, seq;
     int64_t src;
 
     __device__ __forceinline__ RunCursor(const RunTable<MAXRUNS>& t, int n, int32_t slot)
@@ -472,23 +462,77 @@ struct RunCursor {
     __device__ __forceinline__ void load()
     {
         next = tab.dst[r + 1];
-        if (r >= 0) { dst = tab.dst[r]; len = tab.len[r]; seq = tab.seq[r]; src = tab.src[r]; }
-        else        { dst = 0; len = 0; seq = -1; src = 0; }
+        if (r >= 0) { dst = tab.dst[r]; end = tab.end[r]; seq = tab.seq[r]; src = tab.src[r]; }
+        else        { dst = 0; end = 0; seq = -1; src = 0; }
     }
     // frame index of `slot` inside the current run, or -1 on padding
     __device__ __forceinline__ int32_t seek(int32_t slot)
     {
         while (slot >= next) { ++r; load(); }
-        const int64_t t = (int64_t)slot - dst;
-        return (r >= 0 && t < len) ? (int32_t)t : -1;
+        return (r >= 0 && slot < end) ? slot - dst : -1;
     }
+};
+
+// A whole tile of kNarrowSlots slots that lies inside one run (`r`), or inside the padding
+// behind a block's last run (`r` null): four slots of the start table and, per step, one
+// 16-byte vector of payload per lane, without a look at any table.
+__device__ __forceinline__ void narrow_uniform_tile(const PackArgs& a, int64_t g0, const Run* r)
+{
+    const int tid = (int)threadIdx.x;
+    const int64_t g = g0 + 4 * tid;
+    vec16 vs = {~0u, ~0u, ~0u, ~0u}, vf = vs;
+    uint32_t rs = 0, vl = 0;
+    if (r) {
+        const uint32_t fid = (uint32_t)(g - r->dst);               // >= 0: the run begins at or before the tile
+        vs = vec16{(uint32_t)r->seq, (uint32_t)r->seq, (uint32_t)r->seq, (uint32_t)r->seq};
+        vf = vec16{fid, fid + 1u, fid + 2u, fid + 3u};
+        rs = fid == 0u ? 1u : 0u;
+        vl = 0x01010101u;
+    }
+    store_stream(reinterpret_cast<vec16*>(a.seq_id + g), vs);
+    store_stream(reinterpret_cast<vec16*>(a.frame_idx + g), vf);
+    __builtin_nontemporal_store(rs, reinterpret_cast<uint32_t*>(a.reset + g));
+    __builtin_nontemporal_store(vl, reinterpret_cast<uint32_t*>(a.valid + g));
+
+    const int64_t F = a.frame_bytes;
+    vec16* dst = reinterpret_cast<vec16*>(a.packed + g0 * F);      // 16-byte aligned: g0 is a multiple of 1024
+    const int32_t nvec = (int32_t)(kNarrowSlots * F / 16);
+    if (r) {
+        const uint8_t* from = a.src + (r->src + (g0 - r->dst)) * F;
+        for (int32_t v = tid; v < nvec; v += kThreads)
+            store_stream(dst + v, __builtin_nontemporal_load(reinterpret_cast<const vec16_unaligned*>(from) + v));
+    } else {
+        const vec16 z = {0u, 0u, 0u, 0u};
+        for (int32_t v = tid; v < nvec; v += kThreads) store_stream(dst + v, z);
+    }
+}
+
+// A 16-byte vector put together from elements of type E (1, 2, 4 or 16 bytes).  Element numbers
+// are compile-time constants where it is used, so the vector stays in registers.
+template <typename E>
+struct Assembled {
+    vec16 vec = {0u, 0u, 0u, 0u};
+    __device__ __forceinline__ void set(int e, E v)
+    {
+        vec[e * (int)sizeof(E) / 4] |= (uint32_t)v << (8 * (e * (int)sizeof(E) % 4));
+    }
+    __device__ __forceinline__ E get(int e) const
+    {
+        return (E)(vec[e * (int)sizeof(E) / 4] >> (8 * (e * (int)sizeof(E) % 4)));
+    }
+};
+template <>
+struct Assembled<vec16> {
+    vec16 vec = {0u, 0u, 0u, 0u};
+    __device__ __forceinline__ void set(int, vec16 v) { vec = v; }
+    __device__ __forceinline__ vec16 get(int) const { return vec; }
 };
 
 // FUSED (4-byte frames, e.g. tokens): the four slots of a lane's start-table
 // quad are also exactly one 16-byte vector of payload, so both are written in
 // the same pass and the payload pass is skipped.
 template <typename E, bool FUSED>
-__global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a,
+__global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a, const Run* __restrict__ runs,
                                                                const int32_t* __restrict__ first_pos)
 {
     __shared__ RunTable<kNarrowMaxRuns> tab;
@@ -497,9 +541,23 @@ __global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a,
     const int64_t g0 = (int64_t)tile * kNarrowSlots;
     const int64_t g1 = min(g0 + kNarrowSlots, a.total_slots);
     const int nslot = (int)(g1 - g0);
+    const int32_t first = min(max(first_pos[tile], 0), a.n_seq);
 
-    gather_runs(a, min(max(first_pos[tile], 0), a.n_seq), g0, g1, tab);
-    const int n = tab.n;
+    // The two most common tiles where sequences are long need no table: a tile inside one run,
+    // and a tile inside the padding behind its block's last run.  The tile's entry names the
+    // last run of the tile's first block that begins at or before the tile; that record alone
+    // tells (runs of a block follow each other without a gap).  Two wave-uniform look-ups, no
+    // LDS, no barrier: every wave decides alone and all decide alike.
+    if (nslot == kNarrowSlots && first < a.n_seq) {
+        const Run r = runs[first];
+        if (r.dst != kNoRun) {
+            if (r.dst <= g0 && r.dst + r.len >= g1) { narrow_uniform_tile(a, g0, &r); return; }
+            if (r.dst + r.len <= g0 && ((int64_t)r.block + 1) * a.t_blk >= g1) { narrow_uniform_tile(a, g0, nullptr); return; }
+        }
+    }
+
+    const int32_t last = (tile + 1 < gridDim.x) ? min(max(first_pos[tile + 1], 0), a.n_seq) : a.n_seq - 1;
+    const int n = gather_runs(runs, a.n_seq, first, last, g0, g1, tab);
 
     // start table: 4 consecutive slots per lane -> 16-byte / 4-byte stores
     for (int q = tid; 4 * q < nslot; q += kThreads) {
@@ -515,16 +573,18 @@ __global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a,
         }
         if (FUSED && s0 + 4 <= nslot) {
             const uint32_t* src32 = reinterpret_cast<const uint32_t*>(a.src);
-            vec16 pv = {0u, 0u, 0u, 0u};
+            vec16 pv;
             if (fid[0] >= 0 && sid[3] == sid[0] && fid[3] == fid[0] + 3) {
                 // one run: 16 contiguous source bytes (4-byte aligned)
                 typedef vec16 __attribute__((aligned(4))) vec16_a4;
                 pv = __builtin_nontemporal_load(reinterpret_cast<const vec16_a4*>(src32 + from[0]));
             } else {
-                if (fid[0] >= 0) pv.x = src32[from[0]];
-                if (fid[1] >= 0) pv.y = src32[from[1]];
-                if (fid[2] >= 0) pv.z = src32[from[2]];
-                if (fid[3] >= 0) pv.w = src32[from[3]];
+                uint32_t e0 = 0u, e1 = 0u, e2 = 0u, e3 = 0u;
+                if (fid[0] >= 0) e0 = src32[from[0]];
+                if (fid[1] >= 0) e1 = src32[from[1]];
+                if (fid[2] >= 0) e2 = src32[from[2]];
+                if (fid[3] >= 0) e3 = src32[from[3]];
+                pv = vec16{e0, e1, e2, e3};
             }
             store_stream(reinterpret_cast<vec16*>(a.packed + (g0 + s0) * 4), pv);
         }
@@ -564,7 +624,7 @@ __global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a,
         int32_t j = w - slot * k;
         RunCursor<kNarrowMaxRuns> cur(tab, n, slot);
         const int nvalid = min(EPV, tile_elems - w);
-        union { vec16 vec; E e[EPV]; } u;
+        Assembled<E> u;
 #pragma unroll
         for (int e = 0; e < EPV; ++e) {
             E val{};
@@ -573,12 +633,14 @@ __global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a,
                 if (t >= 0) val = src[(cur.src + t) * k + j];
                 if (++j == k) { j = 0; ++slot; }
             }
-            u.e[e] = val;
+            u.set(e, val);
         }
         if (nvalid == EPV) {
             store_stream(reinterpret_cast<vec16*>(dst_tile) + v, u.vec);
         } else {
-            for (int e = 0; e < nvalid; ++e) reinterpret_cast<E*>(dst_tile)[w + e] = u.e[e];
+#pragma unroll
+            for (int e = 0; e < EPV; ++e)
+                if (e < nvalid) reinterpret_cast<E*>(dst_tile)[w + e] = u.get(e);
         }
     }
 }
@@ -754,15 +816,15 @@ bload_status pack_enqueue(const PackLayout& l, const void* d_src, const int64_t*
     if (l.wide) {
         hipLaunchKernelGGL(pack_wide_kernel, grid, block, 0, stream, a, runs, first_pos, kWideTile, inv_unit);
     } else if (frame_bytes % 16 == 0 && aligned_to(d_src, 16)) {
-        hipLaunchKernelGGL((pack_narrow_kernel<vec16, false>), grid, block, 0, stream, a, first_pos);
+        hipLaunchKernelGGL((pack_narrow_kernel<vec16, false>), grid, block, 0, stream, a, runs, first_pos);
     } else if (frame_bytes == 4 && aligned_to(d_src, 4)) {
-        hipLaunchKernelGGL((pack_narrow_kernel<uint32_t, true>), grid, block, 0, stream, a, first_pos);
+        hipLaunchKernelGGL((pack_narrow_kernel<uint32_t, true>), grid, block, 0, stream, a, runs, first_pos);
     } else if (frame_bytes % 4 == 0 && aligned_to(d_src, 4)) {
-        hipLaunchKernelGGL((pack_narrow_kernel<uint32_t, false>), grid, block, 0, stream, a, first_pos);
+        hipLaunchKernelGGL((pack_narrow_kernel<uint32_t, false>), grid, block, 0, stream, a, runs, first_pos);
     } else if (frame_bytes % 2 == 0 && aligned_to(d_src, 2)) {
-        hipLaunchKernelGGL((pack_narrow_kernel<uint16_t, false>), grid, block, 0, stream, a, first_pos);
+        hipLaunchKernelGGL((pack_narrow_kernel<uint16_t, false>), grid, block, 0, stream, a, runs, first_pos);
     } else {
-        hipLaunchKernelGGL((pack_narrow_kernel<uint8_t, false>), grid, block, 0, stream, a, first_pos);
+        hipLaunchKernelGGL((pack_narrow_kernel<uint8_t, false>), grid, block, 0, stream, a, runs, first_pos);
     }
     return launch_status();
 }
