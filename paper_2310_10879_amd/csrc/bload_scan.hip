@@ -41,6 +41,7 @@ struct ScanArgs {
     float* carry;                      // [B, chunks_per_block - 1, feat_dim]: tail states, then states handed on
     uint8_t* has_boundary;             // [B, chunks_per_block - 1]
     int64_t num_blocks;
+    int64_t total_slots;               // num_blocks * t_blk
     int32_t t_blk;
     int32_t feat_dim;
     int32_t chunk;                     // slots per chunk
@@ -78,43 +79,49 @@ template <typename ElemT> union ScanQuad {
     ElemT e[4];
 };
 
-// Flags of 8 consecutive slots starting at `t` of a block of `T` slots (`plane` points at
-// the block's first flag): bit u set iff the flag of slot t + u is non-zero; slots at or
-// behind T read as 0.  One 8-byte load that never leaves the block.
-__device__ __forceinline__ uint32_t scan_flags8(const uint8_t* __restrict__ plane, int32_t t, int32_t T)
+// Flags of the 8 consecutive slots from global slot g on (`plane` covers `total` slots): bit u set
+// iff the flag of slot g + u is non-zero; slots at or behind `total` read as 0.  One 8-byte load
+// that never leaves the plane; a non-zero byte becomes a 1, and two byte-wise dot products with
+// the weights 1, 2, 4, ... gather the eight 1s into eight bits.  TINY: the plane holds fewer than
+// 8 slots, which are read one by one.
+template <bool TINY>
+__device__ __forceinline__ uint32_t scan_flags8(const uint8_t* __restrict__ plane, int64_t g, int64_t total)
 {
     typedef uint64_t word_any __attribute__((aligned(1)));
     uint64_t w;
-    if (T >= 8) {
-        const int32_t from = min(t, T - 8);
-        w = *reinterpret_cast<const word_any*>(plane + from) >> (8 * (t - from));
+    if (!TINY) {
+        const int64_t from = min(g, total - 8);
+        w = *reinterpret_cast<const word_any*>(plane + from) >> (8 * (int)(g - from));
     } else {
         w = 0;
-        for (int u = 0; u < 8; ++u) w |= (uint64_t)plane[min(t + u, T - 1)] << (8 * u);
-        if (T - t < 8) w &= ~0ull >> (8 * (8 - (T - t)));
+        for (int u = 0; u < 8; ++u)
+            if (g + u < total) w |= (uint64_t)plane[g + u] << (8 * u);
     }
-    // non-zero byte -> its top bit -> one bit per byte
-    const uint64_t low7 = 0x7f7f7f7f7f7f7f7full;
-    const uint64_t top = ((w & low7) + low7 | w) & ~low7;
-    return (uint32_t)(((top >> 7) * 0x0102040810204080ull) >> 56);
+    const uint32_t lo = (uint32_t)w, hi = (uint32_t)(w >> 32);
+    const uint32_t lo1 = ((((lo & 0x7f7f7f7fu) + 0x7f7f7f7fu) | lo) >> 7) & 0x01010101u;
+    const uint32_t hi1 = ((((hi & 0x7f7f7f7fu) + 0x7f7f7f7fu) | hi) >> 7) & 0x01010101u;
+    return __builtin_amdgcn_udot4(hi1, 0x80402010u, __builtin_amdgcn_udot4(lo1, 0x08040201u, 0u, false), false);
 }
 
-// Flags of the kScanBatch slots from t on, and which of them are boundaries: padding, a start
-// flag, the block's first slot, or the slot after padding.  `before`: was slot t - 1 valid.
+// Flags of the kScanBatch slots from slot t of a block on (g = the same slot counted over all
+// blocks), and which of them are boundaries: padding, a start flag, the block's first slot, or
+// the slot after padding.  Slots behind the block's end read as 0.  `before`: was slot t - 1 valid.
 struct ScanFlags { uint32_t valid, boundary; };
+template <bool TINY>
 __device__ __forceinline__ ScanFlags scan_flags(const uint8_t* __restrict__ valid,
-                                                const uint8_t* __restrict__ reset, int32_t t, int32_t T,
-                                                uint32_t before)
+                                                const uint8_t* __restrict__ reset, int64_t g, int64_t total,
+                                                int32_t t, int32_t T, uint32_t before)
 {
     const uint32_t in_range = T - t >= kScanBatch ? kScanAll : (1u << (T - t)) - 1u;
     uint32_t vm = 0, rm = 0;
 #pragma unroll
     for (int part = 0; part < kScanBatch; part += 8) {
         if (part == 0 || t + part < T) {
-            vm |= scan_flags8(valid, t + part, T) << part;
-            rm |= scan_flags8(reset, t + part, T) << part;
+            vm |= scan_flags8<TINY>(valid, g + part, total) << part;
+            rm |= scan_flags8<TINY>(reset, g + part, total) << part;
         }
     }
+    vm &= in_range;
     const uint32_t prev_valid = (vm << 1) | before;
     return ScanFlags{vm, in_range & (~vm | rm | ~prev_valid | (t == 0 ? 1u : 0u))};
 }
@@ -122,7 +129,7 @@ __device__ __forceinline__ ScanFlags scan_flags(const uint8_t* __restrict__ vali
 // What a lane works on.  It holds QUADS quads of a frame: quad g of lane r in a row of
 // `row_lanes` lanes is quad number tile_base + g * row_lanes + r, so that each load and each
 // store instruction of a row covers one contiguous stretch of the frame.
-template <typename ElemT, int QUADS, bool VEC>
+template <typename ElemT, int QUADS, bool VEC, bool TINY>
 struct ScanLane {
     static constexpr int EPL = VEC ? QUADS * 4 : 1;      // elements per lane
     bool idle;
@@ -154,39 +161,41 @@ struct ScanLane {
         for (int g = 0; g < QUADS; ++g) quad_on[g] = !VEC || first + g * a.row_lanes < a.n_vec;
     }
 
-    // kScanBatch slots from t on (slots behind the block's end re-read its last slot): the
-    // recurrence goes on in h; `keep` slots are handed to `emit(u, g, quad)`.
-    template <typename Emit>
-    __device__ __forceinline__ void step(const ScanArgs& a, const uint8_t* __restrict__ frames, int32_t t,
+    // kScanBatch slots from t on: the recurrence goes on in h; the first `keep` slots are handed
+    // to `emit(u, g, quad)`.  `at`: the lane's first byte of slot t.  FULL: all kScanBatch slots
+    // lie in the block and all are kept, which spares every clamp and test; otherwise slots
+    // behind the block's end re-read its last slot.  A batch of nothing but padding (block
+    // tails) costs no read: every state ends there and every output is 0.  h = decay * h + x is
+    // one fused multiply-add (one rounding), the state of a boundary slot being replaced by 0
+    // first (never multiplied: it may be infinite).
+    template <bool FULL, typename Emit>
+    __device__ __forceinline__ void step(const ScanArgs& a, const uint8_t* __restrict__ at, int32_t t,
                                          ScanFlags f, float (&h)[EPL], int keep, Emit emit) const
     {
         const int64_t frame_bytes = (int64_t)a.feat_dim * (int64_t)sizeof(ElemT);
-        const uint8_t* src = frames + first_elem * (int64_t)sizeof(ElemT);
-        // A batch of nothing but padding (block tails) must not cost HBM reads.  With one or two
-        // loads per slot it is skipped by a branch (measured on 320-byte float frames: 13.9 ->
-        // 10.4 ms); with four (byte payloads) the branch costs more than it saves in blocks that
-        // are mostly full, so there the loads stay unconditional and re-read the block's first
-        // frame, which sits in the cache.
-        const bool wanted = f.valid != 0;
-        constexpr bool kSkipByBranch = QUADS <= 2;
+        if (f.valid == 0) {
+#pragma unroll
+            for (int k = 0; k < EPL; ++k) h[k] = 0.0f;
+            const float4v zero = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int u = 0; u < kScanBatch; ++u) {
+#pragma unroll
+                for (int g = 0; g < (VEC ? QUADS : 1); ++g)
+                    if ((FULL || u < keep) && quad_on[g]) emit(u, g, zero);
+            }
+            return;
+        }
+        const int32_t last = a.t_blk - 1 - t;              // the block's last slot, counted from t
         if (VEC) {
             ScanQuad<ElemT> x[kScanBatch][QUADS];
-            if (!kSkipByBranch || wanted) {
 #pragma unroll
-                for (int u = 0; u < kScanBatch; ++u) {
-                    const uint8_t* frame = src + (int64_t)(wanted ? min(t + u, a.t_blk - 1) : 0) * frame_bytes;
+            for (int u = 0; u < kScanBatch; ++u) {
+                const uint8_t* frame = at + (int64_t)(FULL ? u : min(u, last)) * frame_bytes;
 #pragma unroll
-                    for (int g = 0; g < QUADS; ++g) {
-                        const int64_t at = quad_on[g] ? (int64_t)g * quad_stride * (int64_t)sizeof(ElemT) : 0;
-                        x[u][g].bits = __builtin_nontemporal_load(
-                            reinterpret_cast<const typename ScanBits<sizeof(ElemT) * 4>::T*>(frame + at));
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int u = 0; u < kScanBatch; ++u) {
-#pragma unroll
-                    for (int g = 0; g < QUADS; ++g) x[u][g].bits = typename ScanBits<sizeof(ElemT) * 4>::T{};
+                for (int g = 0; g < QUADS; ++g) {
+                    const int64_t off = quad_on[g] ? (int64_t)g * quad_stride * (int64_t)sizeof(ElemT) : 0;
+                    x[u][g].bits = __builtin_nontemporal_load(
+                        reinterpret_cast<const typename ScanBits<sizeof(ElemT) * 4>::T*>(frame + off));
                 }
             }
 #pragma unroll
@@ -198,45 +207,62 @@ struct ScanLane {
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const float xv = is_valid ? ScanElem<ElemT>::get(x[u][g].e[j]) : 0.0f;
-                        h[g * 4 + j] = (starts ? 0.0f : a.decay * h[g * 4 + j]) + xv;
+                        h[g * 4 + j] = __builtin_fmaf(a.decay, starts ? 0.0f : h[g * 4 + j], xv);
                         o[j] = h[g * 4 + j];
                     }
-                    if (u < keep && quad_on[g]) emit(u, g, o);
+                    if ((FULL || u < keep) && quad_on[g]) emit(u, g, o);
                 }
             }
         } else {
             ElemT x[kScanBatch];
 #pragma unroll
             for (int u = 0; u < kScanBatch; ++u)
-                x[u] = *reinterpret_cast<const ElemT*>(src + (int64_t)(wanted ? min(t + u, a.t_blk - 1) : 0) * frame_bytes);
+                x[u] = *reinterpret_cast<const ElemT*>(at + (int64_t)(FULL ? u : min(u, last)) * frame_bytes);
 #pragma unroll
             for (int u = 0; u < kScanBatch; ++u) {
                 const bool is_valid = (f.valid >> u) & 1u, starts = (f.boundary >> u) & 1u;
                 const float xv = is_valid ? ScanElem<ElemT>::get(x[u]) : 0.0f;
-                h[0] = (starts ? 0.0f : a.decay * h[0]) + xv;
+                h[0] = __builtin_fmaf(a.decay, starts ? 0.0f : h[0], xv);
                 float4v o = {h[0], 0.0f, 0.0f, 0.0f};
-                if (u < keep) emit(u, 0, o);
+                if (FULL || u < keep) emit(u, 0, o);
             }
+        }
+    }
+
+    // The recurrence over the slots [from, t1) of the lane's block from the state in h, batch by
+    // batch.  `emit(t, n, u, g, quad)`: slot t + u of a batch of n slots that begins at slot t.
+    template <typename Emit>
+    __device__ __forceinline__ void recur(const ScanArgs& a, int32_t from, int32_t t1, float (&h)[EPL], Emit emit) const
+    {
+        const int64_t frame_bytes = (int64_t)a.feat_dim * (int64_t)sizeof(ElemT);
+        const int64_t slot0 = block * a.t_blk;
+        const uint8_t* at = a.packed + ((slot0 + from) * a.feat_dim + first_elem) * (int64_t)sizeof(ElemT);
+        uint32_t before = from > 0 ? (a.valid[slot0 + from - 1] != 0) : 0u;
+        for (int32_t t = from; t < t1; t += kScanBatch, at += (int64_t)kScanBatch * frame_bytes) {
+            const ScanFlags f = scan_flags<TINY>(a.valid, a.reset, slot0 + t, a.total_slots, t, a.t_blk, before);
+            const int n = min(kScanBatch, t1 - t);
+            auto out = [&](int u, int g, float4v o) { emit(t, n, u, g, o); };
+            if (n == kScanBatch) step<true>(a, at, t, f, h, n, out);
+            else step<false>(a, at, t, f, h, n, out);
+            before = (f.valid >> (n - 1)) & 1u;
         }
     }
 };
 
 // The state a chunk hands on when it receives none, and whether it holds a boundary.
-template <typename ElemT, int QUADS, bool VEC>
+template <typename ElemT, int QUADS, bool VEC, bool TINY>
 __global__ __launch_bounds__(kThreads) void scan_tail_kernel(ScanArgs a)
 {
-    typedef ScanLane<ElemT, QUADS, VEC> Lane;
+    typedef ScanLane<ElemT, QUADS, VEC, TINY> Lane;
     const Lane me(a, a.chunks_per_block - 1);                 // the block's last chunk hands nothing on
     if (me.idle) return;
     const int64_t slot0 = me.block * a.t_blk;
-    const uint8_t* __restrict__ valid = a.valid + slot0;
-    const uint8_t* __restrict__ reset = a.reset + slot0;
 
     // the chunk's last boundary
     int32_t last = -1;
-    uint32_t before = me.t0 > 0 ? (valid[me.t0 - 1] != 0) : 0u;
+    uint32_t before = me.t0 > 0 ? (a.valid[slot0 + me.t0 - 1] != 0) : 0u;
     for (int32_t t = me.t0; t < me.t1; t += kScanBatch) {
-        const ScanFlags f = scan_flags(valid, reset, t, a.t_blk, before);
+        const ScanFlags f = scan_flags<TINY>(a.valid, a.reset, slot0 + t, a.total_slots, t, a.t_blk, before);
         const int n = min(kScanBatch, me.t1 - t);
         const uint32_t mine = f.boundary & ((1u << n) - 1u);
         if (mine) last = t + 31 - __builtin_clz(mine);
@@ -249,20 +275,12 @@ __global__ __launch_bounds__(kThreads) void scan_tail_kernel(ScanArgs a)
 #pragma unroll
     for (int k = 0; k < Lane::EPL; ++k) h[k] = 0.0f;
     float* carry = a.carry + (me.block * (a.chunks_per_block - 1) + me.chunk) * (int64_t)a.feat_dim + me.first_elem;
-    before = from > 0 ? (valid[from - 1] != 0) : 0u;
-    for (int32_t t = from; t < me.t1; t += kScanBatch) {
-        const ScanFlags f = scan_flags(valid, reset, t, a.t_blk, before);
-        const int n = min(kScanBatch, me.t1 - t);
-        const bool ends = t + n >= me.t1;
-        me.step(a, a.packed + slot0 * a.feat_dim * (int64_t)sizeof(ElemT), t, f, h, n,
-                [&](int u, int g, float4v o) {
-                    if (ends && u == n - 1) {
-                        if (VEC) *reinterpret_cast<float4v*>(carry + g * me.quad_stride) = o;
-                        else carry[0] = o[0];
-                    }
-                });
-        before = (f.valid >> (n - 1)) & 1u;
-    }
+    me.recur(a, from, me.t1, h, [&](int32_t t, int n, int u, int g, float4v o) {
+        if (t + n >= me.t1 && u == n - 1) {
+            if (VEC) *reinterpret_cast<float4v*>(carry + g * me.quad_stride) = o;
+            else carry[0] = o[0];
+        }
+    });
     if (me.first_elem == 0) a.has_boundary[me.block * (a.chunks_per_block - 1) + me.chunk] = last >= 0;
 }
 
@@ -285,15 +303,12 @@ __global__ __launch_bounds__(kThreads) void scan_chain_kernel(ScanArgs a)
 }
 
 // The recurrence over a chunk's own slots, from the state handed in.
-template <typename ElemT, int QUADS, bool VEC>
+template <typename ElemT, int QUADS, bool VEC, bool TINY>
 __global__ __launch_bounds__(kThreads) void scan_apply_kernel(ScanArgs a)
 {
-    typedef ScanLane<ElemT, QUADS, VEC> Lane;
+    typedef ScanLane<ElemT, QUADS, VEC, TINY> Lane;
     const Lane me(a, a.chunks_per_block);
     if (me.idle) return;
-    const int64_t slot0 = me.block * a.t_blk;
-    const uint8_t* __restrict__ valid = a.valid + slot0;
-    const uint8_t* __restrict__ reset = a.reset + slot0;
     float h[Lane::EPL];
 #pragma unroll
     for (int k = 0; k < Lane::EPL; ++k) h[k] = 0.0f;
@@ -313,24 +328,18 @@ __global__ __launch_bounds__(kThreads) void scan_apply_kernel(ScanArgs a)
             }
         }
     }
-    float* dst = a.out + slot0 * (int64_t)a.feat_dim + me.first_elem;
-    uint32_t before = me.t0 > 0 ? (valid[me.t0 - 1] != 0) : 0u;
-    for (int32_t t = me.t0; t < me.t1; t += kScanBatch) {
-        const ScanFlags f = scan_flags(valid, reset, t, a.t_blk, before);
-        const int n = min(kScanBatch, me.t1 - t);
-        me.step(a, a.packed + slot0 * a.feat_dim * (int64_t)sizeof(ElemT), t, f, h, n,
-                [&](int u, int g, float4v o) {
-                    float* to = dst + (int64_t)(t + u) * a.feat_dim;
-                    if (VEC) __builtin_nontemporal_store(o, reinterpret_cast<float4v*>(to + g * me.quad_stride));
-                    else __builtin_nontemporal_store(o[0], to);
-                });
-        before = (f.valid >> (n - 1)) & 1u;
-    }
+    float* dst = a.out + me.block * a.t_blk * (int64_t)a.feat_dim + me.first_elem;
+    me.recur(a, me.t0, me.t1, h, [&](int32_t t, int, int u, int g, float4v o) {
+        float* to = dst + (int64_t)(t + u) * a.feat_dim;
+        if (VEC) __builtin_nontemporal_store(o, reinterpret_cast<float4v*>(to + g * me.quad_stride));
+        else __builtin_nontemporal_store(o[0], to);
+    });
 }
 
 struct ScanPlan {
     int32_t epv, n_vec, row_lanes, feat_tiles, chunk, chunks_per_block;
     int64_t rows_per_wave;
+    bool tiny;
     size_t carry_bytes, bytes;         // workspace: the states handed on, then the boundary marks
 };
 
@@ -339,6 +348,8 @@ static ScanPlan scan_plan(int64_t num_blocks, int32_t t_blk, int64_t feat_dim, s
     ScanPlan p{};
     // whole 16-byte pieces per frame: a lane takes 16 / elem elements as quads; else one element
     p.epv = (feat_dim * (int64_t)elem) % 16 == 0 ? (int32_t)(16 / elem) : 1;
+    p.tiny = num_blocks * t_blk < 8;               // flags cannot be read eight at a time
+    if (p.tiny) p.epv = 1;
     p.n_vec = p.epv > 1 ? (int32_t)(feat_dim / 4) : (int32_t)feat_dim;      // quads, or elements
     const int64_t per_lane = p.epv > 1 ? p.epv / 4 : 1;
     p.row_lanes = 1;
@@ -373,15 +384,17 @@ static void scan_launch(const ScanArgs& a, const ScanPlan& p, hipStream_t stream
     if (p.chunks_per_block > 1) {
         const int64_t waves = ceil_div(a.num_blocks * (p.chunks_per_block - 1), p.rows_per_wave) * p.feat_tiles;
         const dim3 grid((uint32_t)ceil_div(waves, waves_per_group));
-        if (p.epv > 1) hipLaunchKernelGGL((scan_tail_kernel<ElemT, kQuads, true>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((scan_tail_kernel<ElemT, 1, false>), grid, block, 0, stream, a);
+        if (p.epv > 1) hipLaunchKernelGGL((scan_tail_kernel<ElemT, kQuads, true, false>), grid, block, 0, stream, a);
+        else if (!p.tiny) hipLaunchKernelGGL((scan_tail_kernel<ElemT, 1, false, false>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((scan_tail_kernel<ElemT, 1, false, true>), grid, block, 0, stream, a);
         hipLaunchKernelGGL(scan_chain_kernel, dim3((uint32_t)ceil_div(a.num_blocks * a.feat_dim, kThreads)),
                            block, 0, stream, a);
     }
     const int64_t waves = ceil_div(a.num_blocks * p.chunks_per_block, p.rows_per_wave) * p.feat_tiles;
     const dim3 grid((uint32_t)ceil_div(waves, waves_per_group));
-    if (p.epv > 1) hipLaunchKernelGGL((scan_apply_kernel<ElemT, kQuads, true>), grid, block, 0, stream, a);
-    else hipLaunchKernelGGL((scan_apply_kernel<ElemT, 1, false>), grid, block, 0, stream, a);
+    if (p.epv > 1) hipLaunchKernelGGL((scan_apply_kernel<ElemT, kQuads, true, false>), grid, block, 0, stream, a);
+    else if (!p.tiny) hipLaunchKernelGGL((scan_apply_kernel<ElemT, 1, false, false>), grid, block, 0, stream, a);
+    else hipLaunchKernelGGL((scan_apply_kernel<ElemT, 1, false, true>), grid, block, 0, stream, a);
 }
 
 }  // namespace bload
@@ -427,6 +440,7 @@ extern "C" bload_status bload_segment_scan(const void* d_packed, const uint8_t* 
     a.carry = static_cast<float*>(d_workspace);
     a.has_boundary = static_cast<uint8_t*>(d_workspace) + p.carry_bytes;
     a.num_blocks = num_blocks;
+    a.total_slots = num_blocks * (int64_t)t_blk;
     a.t_blk = t_blk;
     a.feat_dim = (int32_t)feat_dim;
     a.chunk = p.chunk;

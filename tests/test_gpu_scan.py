@@ -43,7 +43,9 @@ def gpu_scan(packed_np, reset, valid, D, dtype, decay):
 @pytest.mark.parametrize("dtype", ["u8", "f16", "f32"])
 @pytest.mark.parametrize("B,T,D", [(1, 1, 1), (3, 10, 1), (700, 33, 1), (40, 5000, 1), (9, 4096, 2),
                                    (70, 130, 3), (300, 130, 16), (50, 700, 80), (60, 300, 100),
-                                   (20, 3000, 256), (64, 32, 3072), (5, 257, 1040)])
+                                   (20, 3000, 256), (64, 32, 3072), (5, 257, 1040),
+                                   # fewer than 8 slots in all, exactly 8, blocks shorter than 8 slots
+                                   (2, 3, 5), (1, 7, 4), (1, 8, 4), (3, 5, 8), (11, 7, 16)])
 def test_scan_follows_the_flags(B, T, D, dtype):
     rng = np.random.default_rng(B + T + D)
     for (p_valid, p_reset), decay in zip([(0.85, 0.02), (0.5, 0.3), (1.0, 0.0)], [0.9, -0.5, 1.0]):
