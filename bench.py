@@ -234,9 +234,10 @@ def run_workload(args, wid: int, cold_sets: int = 0) -> dict:
 
 
 def yardsticks() -> dict:
-    """What plain library kernels reach on this GPU in this run, as same-run references for the
-    roofline fractions: an elementwise copy (1 GiB read + 1 GiB written) and a fill (1 GiB
-    written), both torch's own kernels, timed with events."""
+    """What plain kernels reach on this GPU in this run, as same-run references for the roofline
+    fractions: torch's elementwise copy (1 GiB read + 1 GiB written) and fill (1 GiB written),
+    and the streaming kernels of libbload_yardsticks.so, which move bytes in the patterns of the
+    pack, the reduction and the scan without doing anything else."""
     import torch
 
     dev = torch.device("cuda:0")
@@ -259,6 +260,13 @@ def yardsticks() -> dict:
            "fill_GBps": gbps(lambda: b.fill_(0.0), gib),
            "what": "torch elementwise copy (1 GiB read + 1 GiB written) and fill (1 GiB written)"}
     del a, b
+    torch.cuda.empty_cache()
+    # what the kernels' access patterns alone reach: plain streaming kernels of the same shapes
+    try:
+        from paper_2310_10879_amd import yardsticks as ys
+        out["patterns"] = ys.measure(dev)
+    except Exception as exc:                          # a reference figure, never a reason to fail
+        out["patterns"] = {"error": f"{type(exc).__name__}: {exc}"}
     torch.cuda.empty_cache()
     return out
 

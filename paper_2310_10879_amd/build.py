@@ -1,10 +1,11 @@
-"""Build libbload.so (the C-ABI HIP library) in-tree for gfx950.
+"""Build libbload.so (the C-ABI HIP library) and libbload_yardsticks.so (plain streaming
+kernels that a benchmark times beside it) in-tree for gfx950.
 
     python -m paper_2310_10879_amd.build
 
-hipcc cross-compiles without a GPU present.  The shared object lands next to
-this file so that the binding, and a copy of the tree on another machine, find
-it without any install step.
+hipcc cross-compiles without a GPU present.  The shared objects land next to
+this file so that the bindings, and a copy of the tree on another machine, find
+them without any install step.
 """
 from __future__ import annotations
 
@@ -17,6 +18,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libbload.so")
+YS_SRC = os.path.join(PKG, "yardsticks", "bload_yardsticks.hip")
+YS_LIB = os.path.join(PKG, "libbload_yardsticks.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -37,10 +40,14 @@ def build(verbose: bool = True) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
+    cmd = [HIPCC] + FLAGS + ["-o", YS_LIB, YS_SRC]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
     return LIB
 
 
 if __name__ == "__main__":
     build()
-    print("built", LIB)
+    print("built", LIB, "and", YS_LIB)
     sys.exit(0)

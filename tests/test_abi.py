@@ -182,3 +182,49 @@ def test_argument_checks_need_no_gpu(lib):
     assert lib.bload_segment_reduce(p + 1, p, p, p, 2, 8, 4, 0, 0, 4, p, p, 1 << 20, None) == 4
     assert lib.bload_segment_reduce(p, p, p, p, 50, 5000, 1, 2, 0, 4, p, p, 8, None) == 3
     assert lib.bload_segment_reduce(p, p, p, p, 0, 8, 4, 0, 0, 4, p, p, 0, None) == 0
+
+
+# ---- the yardstick library (include/bload_yardsticks.h) ----------------------------------
+
+YS_HEADER = os.path.join(ROOT, "include", "bload_yardsticks.h")
+YS_LIB = os.path.join(ROOT, "paper_2310_10879_amd", "libbload_yardsticks.so")
+
+
+@pytest.fixture(scope="module")
+def ys_lib():
+    if not os.path.exists(YS_LIB):
+        from paper_2310_10879_amd import build
+        build.build(verbose=False)
+    return ctypes.CDLL(YS_LIB)
+
+
+def test_yardstick_library_exports_every_declared_symbol(ys_lib, lib):
+    text = re.sub(r"/\*.*?\*/", "", open(YS_HEADER).read(), flags=re.S)
+    names = sorted(set(re.findall(r"\b(bload_ys_[a-z_]+)\s*\(", text)))
+    assert names == ["bload_ys_copy", "bload_ys_read", "bload_ys_rows", "bload_ys_token_pack"]
+    for name in names:
+        assert hasattr(ys_lib, name), f"{name} is declared in bload_yardsticks.h but not exported"
+        assert not hasattr(lib, name), f"{name} belongs to the yardstick library, not to libbload.so"
+
+
+def test_yardstick_argument_checks_need_no_gpu(ys_lib):
+    vp, i64, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
+    ys_lib.bload_ys_copy.argtypes = [vp, vp, sz, vp]
+    ys_lib.bload_ys_read.argtypes = [vp, sz, vp, vp]
+    ys_lib.bload_ys_token_pack.argtypes = [vp, vp, vp, vp, vp, vp, i64, ctypes.c_int, ctypes.c_int, vp]
+    ys_lib.bload_ys_rows.argtypes = [vp, vp, i64, i64, ctypes.c_int, ctypes.c_int, vp, vp]
+    p = 0x1000                                           # never dereferenced: every call below is refused or empty
+    assert ys_lib.bload_ys_copy(None, p, 16, None) == 1
+    assert ys_lib.bload_ys_copy(p, p, 17, None) == 1     # not a multiple of 16
+    assert ys_lib.bload_ys_copy(p + 4, p, 16, None) == 1  # base not 16-byte aligned
+    assert ys_lib.bload_ys_copy(p, p, 0, None) == 0
+    assert ys_lib.bload_ys_read(p, 16, None, None) == 1
+    assert ys_lib.bload_ys_read(p, 0, p, None) == 0
+    assert ys_lib.bload_ys_token_pack(p, p, p, p, p, p, 4097, 0, 0, None) == 1
+    assert ys_lib.bload_ys_token_pack(p, p, p, p, p, p, 4096, 101, 0, None) == 1
+    assert ys_lib.bload_ys_token_pack(p, p, p, None, p, p, 4096, 0, 0, None) == 1
+    assert ys_lib.bload_ys_token_pack(p, p, p, p, p, p, 0, 0, 0, None) == 0
+    assert ys_lib.bload_ys_rows(p, None, 10, 8 * 16 * 20, 3, 20, p, None) == 1     # rows per wave: 1, 2 or 4
+    assert ys_lib.bload_ys_rows(p, None, 10, 8 * 16 * 20, 2, 33, p, None) == 1     # more lanes than a row has
+    assert ys_lib.bload_ys_rows(p, None, 10, 8 * 16 * 20 + 16, 2, 20, p, None) == 1  # not whole batches
+    assert ys_lib.bload_ys_rows(p, None, 0, 8 * 16 * 20, 2, 20, p, None) == 0
