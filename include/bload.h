@@ -204,9 +204,10 @@ bload_status bload_plan_shard(const int32_t* d_order, const int32_t* d_block_of_
  * d_workspace         device scratch of >= bload_pack_workspace_bytes(...) bytes,
  *                     32-byte aligned: one 32-byte record per sequence (where it
  *                     lands, where it comes from) and one int32 per destination
- *                     tile -- 4 KiB of packed tensor or 1024 slots -- saying where
- *                     the tile starts in the shuffled order; contents meaningless
- *                     afterwards
+ *                     tile -- 4 KiB of packed tensor (plus, from 2^21 slots on, one
+ *                     per 1024 slots for the pass that writes the start table) or
+ *                     1024 slots -- saying where the tile starts in the shuffled
+ *                     order; contents meaningless afterwards
  *
  * Every byte of the five outputs is written exactly once (no prior memset is
  * needed), and nothing outside them whatever the tables hold.  The tables are
@@ -237,10 +238,11 @@ bload_status bload_pack(const void* d_src, const int64_t* d_src_offsets, const i
  * entries -- lives in a fixed array of 16 MiB of device memory that belongs to the
  * loaded library; every GPU on which this entry point is used holds one until the
  * process ends.  Limits: n_seq <= BLOAD_PACK_NOALLOC_MAX_SEQ and at most
- * BLOAD_PACK_NOALLOC_MAX_TILES destination tiles (a tile is 4 KiB of packed tensor
- * when bload_pack_tile_bytes() says 4096, else 1024 slots: 8 GiB of packed tensor,
- * or 2^31 slots); anything larger is refused with BLOAD_EOVERFLOW before anything
- * is launched.  All other arguments, checks and results are those of bload_pack.
+ * BLOAD_PACK_NOALLOC_MAX_TILES - 4 tile entries (a tile is 4 KiB of packed tensor
+ * when bload_pack_tile_bytes() says 4096, with one more entry per 1024 slots from
+ * 2^21 slots on, else 1024 slots: just under 8 GiB of packed tensor, or 2^31
+ * slots); anything larger is refused with BLOAD_EOVERFLOW before anything is
+ * launched.  All other arguments, checks and results are those of bload_pack.
  * The call allocates and frees nothing and does not synchronise.  Nothing in the
  * array has to be cleared between calls (each call rewrites the part it reads),
  * but all calls on one GPU share it: two such calls must not overlap in time on

@@ -224,6 +224,8 @@ __device__ __forceinline__ void write_slots(const PackArgs& a, int64_t lo, int64
     }
 }
 
+constexpr int kTableSlots = 1024;                   // slots per workgroup of the slot-tile kernel
+
 // Pass 1 (used by both tile shapes, which come after it in this file's launch
 // order).  Thread p < n_seq writes the run of shuffled position p.  Thread t < n_tiles
 // finds, for tile t, the last shuffled position of the tile's first block whose
@@ -236,7 +238,7 @@ __global__ __launch_bounds__(kThreads) void pack_prepare_kernel(
     const int32_t* __restrict__ offset_of_seq, const int32_t* __restrict__ block_first,
     int32_t n_seq, int64_t num_blocks, int64_t t_blk, int64_t frame_bytes, int64_t n_tiles,
     int32_t tile_bytes, double inv_frame_bytes, double inv_t_blk, Run* __restrict__ runs,
-    int32_t* __restrict__ first_pos)
+    int32_t* __restrict__ first_pos, int64_t n_table_tiles, int32_t* __restrict__ first_pos_table)
 {
     const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (idx < n_seq) {
@@ -254,8 +256,8 @@ __global__ __launch_bounds__(kThreads) void pack_prepare_kernel(
         }
         runs[idx] = r;
     }
-    if (idx < n_tiles) {
-        const int64_t gs_lo = floor_div(idx * tile_bytes, frame_bytes, inv_frame_bytes);
+    // the last shuffled position of slot gs_lo's block whose sequence starts at or before gs_lo
+    auto entry_of = [&](int64_t gs_lo) {
         const int64_t b0 = floor_div(gs_lo, t_blk, inv_t_blk);
         const int32_t rel = (int32_t)(gs_lo - b0 * t_blk);
         int32_t p = min(max(block_first[b0], 0), n_seq);
@@ -265,8 +267,11 @@ __global__ __launch_bounds__(kThreads) void pack_prepare_kernel(
             const uint32_t i = (uint32_t)order[mid];
             if (i < (uint32_t)n_seq && offset_of_seq[i] <= rel) p = mid; else above = mid;
         }
-        first_pos[idx] = p;
-    }
+        return p;
+    };
+    if (idx < n_tiles) first_pos[idx] = entry_of(floor_div(idx * tile_bytes, frame_bytes, inv_frame_bytes));
+    // tiles of kTableSlots slots, for the pass that writes the start table of wide frames
+    if (idx < n_table_tiles) first_pos_table[idx] = entry_of(idx * kTableSlots);
 }
 
 // Pass 2: the copy.  The run table and the tiles' entries come as separate
@@ -274,7 +279,7 @@ __global__ __launch_bounds__(kThreads) void pack_prepare_kernel(
 // can alias them and keeps their loads on the scalar unit.
 __global__ __launch_bounds__(kThreads) void pack_wide_kernel(
     PackArgs a, const Run* __restrict__ runs, const int32_t* __restrict__ first_pos,
-    int32_t tile_bytes, double inv_frame_bytes)
+    int32_t tile_bytes, double inv_frame_bytes, int32_t writes_table)
 {
     const int64_t F = a.frame_bytes;
     const int64_t T = a.t_blk;
@@ -283,7 +288,7 @@ __global__ __launch_bounds__(kThreads) void pack_wide_kernel(
     const uint32_t tile = xcd_contiguous(blockIdx.x, gridDim.x);
     const int64_t D0 = (int64_t)tile * tile_bytes;
     const int64_t D1 = min(D0 + (int64_t)tile_bytes, total_bytes);
-    const bool table_wave = wave_id() == 0;
+    const bool table_wave = writes_table != 0 && wave_id() == 0;
     int32_t p = min(max(first_pos[tile], 0), n_seq);
 
     // the common case first: the tile lies inside one run -- one load and one
@@ -441,7 +446,7 @@ __global__ __launch_bounds__(kThreads) void pack_wide_kernel(
 
 // ----------------------------------------------------------------- narrow
 
-constexpr int kNarrowSlots = 1024;                  // slots per workgroup
+constexpr int kNarrowSlots = kTableSlots;            // slots per workgroup
 constexpr int kNarrowMaxRuns = kNarrowSlots + 2;
 
 // The run a lane is currently reading from, kept in registers and advanced
@@ -476,7 +481,7 @@ struct RunCursor {
 // A whole tile of kNarrowSlots slots that lies inside one run (`r`), or inside the padding
 // behind a block's last run (`r` null): four slots of the start table and, per step, one
 // 16-byte vector of payload per lane, without a look at any table.
-__device__ __forceinline__ void narrow_uniform_tile(const PackArgs& a, int64_t g0, const Run* r)
+__device__ __forceinline__ void narrow_uniform_tile(const PackArgs& a, int64_t g0, const Run* r, bool payload)
 {
     const int tid = (int)threadIdx.x;
     const int64_t g = g0 + 4 * tid;
@@ -494,6 +499,7 @@ __device__ __forceinline__ void narrow_uniform_tile(const PackArgs& a, int64_t g
     __builtin_nontemporal_store(rs, reinterpret_cast<uint32_t*>(a.reset + g));
     __builtin_nontemporal_store(vl, reinterpret_cast<uint32_t*>(a.valid + g));
 
+    if (!payload) return;
     const int64_t F = a.frame_bytes;
     vec16* dst = reinterpret_cast<vec16*>(a.packed + g0 * F);      // 16-byte aligned: g0 is a multiple of 1024
     const int32_t nvec = (int32_t)(kNarrowSlots * F / 16);
@@ -531,10 +537,13 @@ struct Assembled<vec16> {
 // FUSED (4-byte frames, e.g. tokens): the four slots of a lane's start-table
 // quad are also exactly one 16-byte vector of payload, so both are written in
 // the same pass and the payload pass is skipped.
-template <typename E, bool FUSED>
+// PAYLOAD false: only the start table is written (the table pass of wide frames, whose payload
+// the 4 KiB tiles copy).
+template <typename E, bool FUSED, bool PAYLOAD = true>
 __global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a, const Run* __restrict__ runs,
                                                                const int32_t* __restrict__ first_pos)
 {
+    static_assert(PAYLOAD || !FUSED, "the fused form writes the payload with the table");
     __shared__ RunTable<kNarrowMaxRuns> tab;
     const int tid = (int)threadIdx.x;
     const uint32_t tile = xcd_contiguous(blockIdx.x, gridDim.x);
@@ -551,8 +560,8 @@ __global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a, const
     if (nslot == kNarrowSlots && first < a.n_seq) {
         const Run r = runs[first];
         if (r.dst != kNoRun) {
-            if (r.dst <= g0 && r.dst + r.len >= g1) { narrow_uniform_tile(a, g0, &r); return; }
-            if (r.dst + r.len <= g0 && ((int64_t)r.block + 1) * a.t_blk >= g1) { narrow_uniform_tile(a, g0, nullptr); return; }
+            if (r.dst <= g0 && r.dst + r.len >= g1) { narrow_uniform_tile(a, g0, &r, PAYLOAD); return; }
+            if (r.dst + r.len <= g0 && ((int64_t)r.block + 1) * a.t_blk >= g1) { narrow_uniform_tile(a, g0, nullptr, PAYLOAD); return; }
         }
     }
 
@@ -609,6 +618,7 @@ __global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a, const
         }
     }
 
+    if (!PAYLOAD) return;
     // payload: one 16-byte destination vector per lane and step, assembled
     // from elements of type E (k elements per frame)
     constexpr int EPV = 16 / (int)sizeof(E);
@@ -729,8 +739,16 @@ namespace {
 struct PackLayout {
     bool wide;
     int64_t tiles;
-    size_t runs_off, first_off, bytes;
+    int64_t table_tiles;       // slot tiles of the separate start-table pass (wide frames, large tensors), else 0
+    size_t runs_off, first_off, table_off, bytes;
 };
+
+// From this many slots on, the start table of wide frames is written by a pass of its own, in
+// slot tiles with full-width stores: the few entries per 4 KiB tile, written by that tile's first
+// wave, are 2 % of the bytes and cost 5 % of the time (10^8 slots of 320 bytes: 9.64 ms, 9.11 ms
+// without them, 9.36 ms with the pass).  About 3 ns per 1000 slots: below a couple of million
+// slots the pass saves less than its launch costs, and the one pass stays.
+constexpr int64_t kTablePassFromSlots = (int64_t)1 << 21;
 
 // Sizes the caller cannot know in advance (which tile shape the lengths will choose) are
 // taken at their larger value when `for_query`.
@@ -749,9 +767,11 @@ bool pack_layout(int64_t n_seq, int64_t num_blocks, int32_t t_blk, int64_t frame
         l->wide = takes_wide_tiles(frame_bytes, total_bytes, n_seq, src_aligned16);
         l->tiles = l->wide ? wide_tiles : narrow_tiles;
     }
+    l->table_tiles = l->wide && total_slots >= kTablePassFromSlots ? narrow_tiles : 0;
     l->runs_off = 0;
     l->first_off = round_up((size_t)n_seq * sizeof(Run), 32);
-    l->bytes = l->first_off + round_up((size_t)l->tiles * sizeof(int32_t), 16);
+    l->table_off = l->first_off + round_up((size_t)l->tiles * sizeof(int32_t), 16);
+    l->bytes = l->table_off + round_up((size_t)l->table_tiles * sizeof(int32_t), 16);
     return true;
 }
 
@@ -786,9 +806,10 @@ bload_status pack_enqueue(const PackLayout& l, const void* d_src, const int64_t*
                           int32_t* d_seq_id, int32_t* d_frame_idx, uint8_t* d_reset, uint8_t* d_valid,
                           uint8_t* ws, hipStream_t stream)
 {
-    if (l.tiles > INT32_MAX) return BLOAD_EOVERFLOW;
+    if (l.tiles > INT32_MAX || l.table_tiles > INT32_MAX) return BLOAD_EOVERFLOW;
     Run* runs = reinterpret_cast<Run*>(ws + l.runs_off);
     int32_t* first_pos = reinterpret_cast<int32_t*>(ws + l.first_off);
+    int32_t* first_pos_table = reinterpret_cast<int32_t*>(ws + l.table_off);
     PackArgs a;
     a.src = static_cast<const uint8_t*>(d_src);
     a.runs = runs;
@@ -807,14 +828,18 @@ bload_status pack_enqueue(const PackLayout& l, const void* d_src, const int64_t*
     const int64_t unit_bytes = l.wide ? frame_bytes : 1;
     const int32_t tile_units = l.wide ? kWideTile : kNarrowSlots;
     const double inv_unit = 1.0 / (double)unit_bytes, inv_t = 1.0 / (double)t_blk;
-    const int64_t prepare_threads = l.tiles > n_seq ? l.tiles : n_seq;
+    const int64_t prepare_threads = l.tiles > n_seq ? l.tiles : n_seq;       // table_tiles <= tiles
     hipLaunchKernelGGL(pack_prepare_kernel, dim3((uint32_t)ceil_div(prepare_threads, kThreads)),
                        dim3(kThreads), 0, stream, d_src_offsets, d_lengths, d_order, d_block_of_seq,
                        d_offset_of_seq, d_block_first, (int32_t)n_seq, num_blocks, (int64_t)t_blk, unit_bytes,
-                       l.tiles, tile_units, inv_unit, inv_t, runs, first_pos);
+                       l.tiles, tile_units, inv_unit, inv_t, runs, first_pos, l.table_tiles, first_pos_table);
     const dim3 grid((uint32_t)l.tiles), block(kThreads);
     if (l.wide) {
-        hipLaunchKernelGGL(pack_wide_kernel, grid, block, 0, stream, a, runs, first_pos, kWideTile, inv_unit);
+        hipLaunchKernelGGL(pack_wide_kernel, grid, block, 0, stream, a, runs, first_pos, kWideTile, inv_unit,
+                           l.table_tiles == 0 ? 1 : 0);
+        if (l.table_tiles > 0)
+            hipLaunchKernelGGL((pack_narrow_kernel<uint8_t, false, false>), dim3((uint32_t)l.table_tiles), block, 0,
+                               stream, a, runs, first_pos_table);
     } else if (frame_bytes % 16 == 0 && aligned_to(d_src, 16)) {
         hipLaunchKernelGGL((pack_narrow_kernel<vec16, false>), grid, block, 0, stream, a, runs, first_pos);
     } else if (frame_bytes == 4 && aligned_to(d_src, 4)) {
@@ -924,8 +949,10 @@ extern "C" bload_status bload_pack_noalloc(const void* d_src, const int64_t* d_s
     if (!pack_layout(n_seq, num_blocks, t_blk, frame_bytes, aligned_to(d_src, 16), false, &l))
         return BLOAD_EOVERFLOW;
     // the fixed array holds this many runs and tiles, no more
-    if (n_seq > BLOAD_PACK_NOALLOC_MAX_SEQ || l.tiles > BLOAD_PACK_NOALLOC_MAX_TILES) return BLOAD_EOVERFLOW;
+    if (n_seq > BLOAD_PACK_NOALLOC_MAX_SEQ || l.tiles + l.table_tiles + 4 > BLOAD_PACK_NOALLOC_MAX_TILES)
+        return BLOAD_EOVERFLOW;
     l.first_off = kStaticRunBytes;
+    l.table_off = l.first_off + round_up((size_t)l.tiles * sizeof(int32_t), 16);
     uint8_t* ws = nullptr;
     const bload_status got = static_scratch(&ws);
     if (got != BLOAD_OK) return got;

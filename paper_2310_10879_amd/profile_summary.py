@@ -100,8 +100,9 @@ def main() -> None:
     w_scale = CAL_KIB / write[(cal, "WRITE_SIZE")][0]
     rows = ["| kernel | dispatches | FETCH_SIZE KiB (raw) | read GB (scaled) | WRITE_SIZE KiB (raw) | written GB (scaled) |",
             "|---|---|---|---|---|---|"]
-    # kernel families of one library call each: (bench key, kernel name prefix, main kernel prefixes, source file)
-    families = {"pack": ("pack", "bload::pack_", ("bload::pack_wide", "bload::pack_narrow"), "bload_pack.hip"),
+    # kernel families of one library call each: (bench key, kernel name prefix, prefixes of the kernel that
+    # runs exactly once per call, source file)
+    families = {"pack": ("pack", "bload::pack_", ("bload::pack_prepare",), "bload_pack.hip"),
                 "reduce": ("segment_reduce", "bload::reduce_", ("bload::reduce_wide", "bload::reduce_narrow"),
                            "bload_reduce.hip"),
                 "scan": ("segment_scan", "bload::scan_", ("bload::scan_apply",), "bload_scan.hip")}

@@ -119,6 +119,9 @@ def test_argument_checks_need_no_gpu(lib):
     f.argtypes = [i64, i64, i32, i64]
     need = 32 * 1000 + 4 * -(-180 * 600 * 37632 // 4096)     # a 32-byte run per sequence, an int32 per 4 KiB tile
     assert need <= f(1000, 180, 600, 37632) < need + 16 and f(1000, 180, 600, 37632) % 16 == 0
+    # from 2^21 slots on, one more int32 per 1024 slots for the pass that writes the start table
+    need = 32 * 50000 + 4 * -(-34576 * 3000 * 320 // 4096) + 4 * -(-34576 * 3000 // 1024)
+    assert need <= f(50000, 34576, 3000, 320) < need + 32
     assert f(1000, 180, 600, 4) == 32 * 1000 + 4 * -(-180 * 600 // 1024) + 8
     assert f(1000, 0, 600, 4096) == 0 and f(0, 5, 600, 4096) == 0
     assert f(10**6, 200, 8, 64) >= 32 * 10**6 + 4 * 2          # frames that may take either tile shape

@@ -140,3 +140,25 @@ def test_pack_workloads_full_size(wid):
             got = bl.Packed(out.packed[lo:hi], out.seq_id[lo:hi], out.frame_idx[lo:hi],
                             out.reset[lo:hi], out.valid[lo:hi])
             assert_packed_equal(got, ref, f"workload {wid} blocks {lo}:{hi} ")
+
+
+@pytest.mark.parametrize("n,T,F,kind", [(3000, 1000, 68, "long"),      # frames no vector load fits, long runs
+                                        (2000, 3000, 320, "uniform"),  # the shape of the largest workload
+                                        (70000, 64, 516, "mixed")])    # many short runs per tile, blocks of 64
+def test_pack_large_tensors_of_wide_frames(n, T, F, kind, progress):
+    """From 2^21 slots on, 4 KiB tiles copy the payload and a pass of its own writes the start
+    table: every block against the oracle, slab by slab."""
+    from gpu_util import assert_packed_equal_whole
+    bl = binding()
+    rng = np.random.default_rng(n + T + F)
+    L = workloads.random_lengths(rng, n, T, kind)
+    so = workloads.src_offsets(L)
+    src = rng.integers(0, 256, size=int(so[-1]) * F, dtype=np.uint8)
+    ref_plan = oracle.plan(L, T, oracle.order(n, 2))
+    assert ref_plan.num_blocks * T >= 1 << 21
+    assert bl.bload_pack_tile_bytes(n, ref_plan.num_blocks, T, F, True) == 4096
+    plan_dev = upload_plan(ref_plan, n)
+    out = bl.bload_pack(to_dev(src), to_dev(so), to_dev(L), plan_dev, F)
+    torch.cuda.synchronize()
+    assert_packed_equal_whole(out, src, so, L, ref_plan, F, max(1, (64 << 20) // (T * F)),
+                              f"n={n} T={T} F={F} {kind}: ", say=progress)

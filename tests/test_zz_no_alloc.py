@@ -41,6 +41,8 @@ def test_noalloc_pack_equals_pack_on_consecutive_calls():
     assert bl.bload_pack_tile_bytes(4000, big.num_blocks, 600, 4096) == 4096
     assert big.num_blocks * 600 > bl.PACK_NOALLOC_MAX_TILES // 2
     pack_both_ways(bl, 700, 300, 4096, "mixed", 2)                 # smaller, same tile shape
+    wide = pack_both_ways(bl, 3000, 1000, 68, "long", 5)           # 4 KiB tiles and the start table in a pass of its own
+    assert bl.bload_pack_tile_bytes(3000, wide.num_blocks, 1000, 68) == 4096 and wide.num_blocks * 1000 >= 1 << 21
     pack_both_ways(bl, 200000, 64, 4, "short", 3)                  # 1024-slot tiles, many runs
     pack_both_ways(bl, 300, 33, 12, "mixed", 4)                    # smaller again
     pack_both_ways(bl, 4000, 600, 4096, "uniform", 1)              # and the first once more
