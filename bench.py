@@ -183,6 +183,8 @@ def run_workload(args, wid: int, cold_sets: int = 0) -> dict:
         "frames_per_s": local_frames * args.steps / elapsed,
         "work_frames": local_frames,
         "phases_ms": {"plan": plan_ms, "pack": pack_ms, "segment_reduce": reduce_ms},
+        # the planner is a latency-bound chain: per sequence it costs
+        "plan_ns_per_sequence": plan_ms * 1e6 / max(1, N),
         # the whole call: pack_prepare_kernel, the copy kernel and, for 4 KiB tiles over 2^21 slots or more,
         # the pass that writes the start table (pack_narrow_kernel<unsigned char, false, false>)
         "pack": dict(roofline_block(("pack_wide_kernel + start-table pass" if slots >= 1 << 21 else "pack_wide_kernel")
