@@ -393,18 +393,20 @@ __global__ __launch_bounds__(kThreads) void reduce_wide_kernel(ReduceArgs a)
 
 // ----------------------------------------------------------------- narrow
 //
-// Lanes across time: a workgroup takes 4096 consecutive slots (a "tile", which
-// may span several blocks), a lane 16 consecutive slots.  From the flags every
-// lane builds two 16-bit masks: valid, and "break" (a slot that cannot continue
-// the segment of the slot before it: padding, a start flag, a block's first
-// slot, or a slot that follows padding).  Sums are a segmented scan with the
+// Lanes across time: a workgroup takes 4096 consecutive slots (a "tile": a piece
+// of one block, or several whole blocks), a lane 16 consecutive slots.  From the
+// flags every lane builds two 16-bit masks: valid, and "break" (a slot that cannot
+// continue the segment of the slot before it: padding, a start flag, a block's
+// first slot, or a slot that follows padding).  Sums are a segmented scan with the
 // breaks as heads: a lane contributes the sum of its slots from its last break
-// on (all its slots if it has none); the scan runs across the wave without LDS
-// (DPP) and across the four waves through LDS, and gives every lane the sum of
-// the segment that is open in front of it.  Only a lane in which a segment ends
-// -- rare when segments are long -- then walks its 16 slots.  Frame counts need
-// no scan: a segment's frames are consecutive, so its count is (end position -
-// position of its break + 1).  Integer sums are exact, float sums add only the
+// on (`tail`: all its slots if it has none); the scan runs across the wave without
+// LDS (DPP) and across the four waves through LDS, and gives every lane the sum of
+// the segment that is open in front of it.  A lane keeps one more sum, of its
+// slots in front of its first break (`head`), and not its 16 elements: a piece
+// that ends in the lane is carry + head, or tail; only a piece between two breaks
+// of one lane -- a segment of fewer than 16 slots -- is read again.  Frame counts
+// need no scan: a segment's frames are consecutive, so its count is (end position
+// - position of its break + 1).  Integer sums are exact, float sums add only the
 // segment's own terms (no cancellation against neighbouring segments).
 
 constexpr int kSlotsPerLane = 16;
