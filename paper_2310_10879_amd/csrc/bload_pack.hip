@@ -18,10 +18,15 @@
 //          best where runs (a sequence's bytes) are long: a tile inside one run
 //          is a plain copy with wave-uniform scalar look-ups.  Frames of at
 //          least 64 bytes.
-//   narrow a tile is 1024 consecutive slots; the runs go into an LDS table,
-//          lanes take consecutive 16-byte destination vectors and assemble
-//          them from source elements of the widest type that divides the
-//          frame.  Small frames, and middle-sized frames of short sequences.
+//   narrow a tile is 1024 consecutive slots; a tile inside one run or inside a
+//          block's padding is written straight away, for any other the runs go
+//          into an LDS table, lanes take consecutive 16-byte destination vectors
+//          and assemble them from source elements of the widest type that
+//          divides the frame.  Small frames, and middle-sized frames of short
+//          sequences.  Without its payload part the same kernel writes the start
+//          table of large tensors of wide frames, whose 4 KiB tiles then only
+//          copy.
+// All large outputs leave through streaming stores (see store_slot).
 #include "bload_common.hpp"
 
 #include <limits.h>

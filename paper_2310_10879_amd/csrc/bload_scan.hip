@@ -21,7 +21,8 @@
 // A row of lanes (16 input bytes per lane where the frame allows it, taken as quads of 4
 // elements laid out so that every load and store instruction of the row is contiguous; else
 // one element per lane) covers the features; a wavefront holds 64 / row-width rows, each on
-// a chunk of its own.  All loads of a step are unconditional and issued together.
+// a chunk of its own.  All loads of a step (8 slots) are issued together; a step of nothing but
+// padding issues none.
 #include "bload_common.hpp"
 
 #include <hip/hip_fp16.h>
