@@ -358,6 +358,7 @@ def main() -> int:
         "config": {k: head[k] for k in ("workload", "n_seq", "t_blk", "frame_bytes", "total_frames",
                                         "num_blocks", "lengths")},
         "phases_ms": head["phases_ms"],
+        "plan_ns_per_sequence": head["plan_ns_per_sequence"],
         "pack": head["pack"],
         "segment_reduce": head["segment_reduce"],
         "padding": head["padding"],
@@ -368,8 +369,8 @@ def main() -> int:
             result[k] = head[k]
 
     if not args.only and args.world == 1:
-        keep = ("workload", "ms_per_step", "frames_per_s", "phases_ms", "pack", "segment_reduce", "segment_scan",
-                "padding", "setup_s")
+        keep = ("workload", "ms_per_step", "frames_per_s", "phases_ms", "plan_ns_per_sequence", "pack",
+                "segment_reduce", "segment_scan", "padding", "setup_s")
         per = {}
         for wid in (1, 2, 3, 4, 5):
             r = head if wid == args.workload else run_workload(args, wid)
