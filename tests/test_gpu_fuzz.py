@@ -1,6 +1,8 @@
 """Seeded random configurations through the whole path (plan, pack, reduce, scan) against the
 oracle: frame sizes, block lengths, length mixes and seeds that no hand-picked case lists, small
 enough for the oracle to finish each in a moment."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -68,3 +70,13 @@ def test_random_configurations(chunk):
         err = np.abs(h.cpu().numpy().astype(np.float64) - ref_h)
         assert np.all(err <= (3 * k + 4) * EPS * scale), f"scan F={F} T={T}: max err {err.max()}"
         torch.cuda.synchronize()
+
+
+@pytest.mark.skipif("BLOAD_FUZZ_MORE" not in os.environ,
+                    reason="set BLOAD_FUZZ_MORE=first:last to run the same checks on chunks of other seeds")
+def test_more_random_configurations():
+    """The checks above on any further range of seeds, e.g. BLOAD_FUZZ_MORE=5000:5250 (4000
+    configurations, about 7 minutes)."""
+    first, last = (int(v) for v in os.environ["BLOAD_FUZZ_MORE"].split(":"))
+    for chunk in range(first, last):
+        test_random_configurations(chunk)
