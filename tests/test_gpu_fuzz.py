@@ -74,9 +74,10 @@ def test_random_configurations(chunk):
 
 @pytest.mark.skipif("BLOAD_FUZZ_MORE" not in os.environ,
                     reason="set BLOAD_FUZZ_MORE=first:last to run the same checks on chunks of other seeds")
-def test_more_random_configurations():
+def test_more_random_configurations(progress):
     """The checks above on any further range of seeds, e.g. BLOAD_FUZZ_MORE=5000:5250 (4000
-    configurations, about 7 minutes)."""
+    configurations, about 7 minutes; a line per chunk goes past pytest's capture)."""
     first, last = (int(v) for v in os.environ["BLOAD_FUZZ_MORE"].split(":"))
     for chunk in range(first, last):
         test_random_configurations(chunk)
+        progress(f"fuzz chunk {chunk} of {first}:{last} equal to the oracle")
