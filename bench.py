@@ -335,7 +335,13 @@ def main() -> int:
                     help="also run a plain elementwise copy of 1 GiB (read 1 GiB, write 1 GiB) "
                          "three times before the steps, as the known-size kernel that the "
                          "rocprofv3 HBM counters are scaled by")
+    ap.add_argument("--yardsticks-only", action="store_true",
+                    help="time nothing but the yardstick kernels (torch copy and fill, and the streaming "
+                         "kernels of libbload_yardsticks.so) and print their figures as one JSON line")
     args = ap.parse_args()
+    if args.yardsticks_only:
+        print(json.dumps({"yardsticks": yardsticks()}))
+        return 0
     if args.gpus != 1:
         print("bench.py measures one GPU: the packer runs on a single MI355X and the library has "
               "no multi-GPU path (run with --gpus 1)", file=sys.stderr)

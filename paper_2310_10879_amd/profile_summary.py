@@ -49,9 +49,36 @@ def counter_means(path):
     return {k: (sum(v) / len(v), len(v)) for k, v in acc.items()}
 
 
+def yardstick_summary(args) -> None:
+    """Kernel trace of the yardstick kernels beside the rates bench.py computed from its own event timing."""
+    with open(args.bench) as f:
+        ys = json.loads([ln for ln in f if ln.startswith("{")][-1])["yardsticks"]
+    lines = ["# rocprofv3 kernel trace of bench.py's yardstick kernels", "",
+             "Command (on the MI355X, from the repository root; OUT = a scratch directory):", "",
+             "    rocprofv3 --kernel-trace --stats --output-format csv -d $OUT/kt -o kt -- \\",
+             "        python3 bench.py --yardsticks-only", "",
+             "Summarised by `python -m paper_2310_10879_amd.profile_summary --yardsticks` from kt_kernel_stats.csv.",
+             "Each kernel runs twice untimed and five times timed (torch's: three and ten).", "",
+             "| kernel | calls | avg ns | min ns | max ns |", "|---|---|---|---|---|"]
+    with open(args.trace) as f:
+        for r in csv.DictReader(f):
+            name = r["Name"].replace("(anonymous namespace)::", "").split("(")[0].replace("void ", "")
+            if "ys_" in name or "at::native" in name:
+                lines.append(f"| {name[:110]} | {r['Calls']} | {float(r['AverageNs']):.0f} | {r['MinNs']} | {r['MaxNs']} |")
+    lines += ["", "bench.py's figures in the same run (bytes the pattern moves / mean event time, GB/s):", ""]
+    lines += [f"* torch copy {ys['copy_GBps']:.0f}, torch fill {ys['fill_GBps']:.0f}"]
+    for key, val in ys["patterns"].items():
+        if key != "what":
+            lines.append(f"* {key[:-5] if key.endswith('_GBps') else key}: {val:.0f}" if isinstance(val, float) else f"* {key}: {val}")
+    lines += ["", ys["patterns"].get("what", "")]
+    with open(os.path.join(ROOT, "profiles", "bload_yardsticks_kernel_trace.md"), "w") as f:
+        f.write("\n".join(lines) + "\n")
+    print(lines[-3])
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", type=int, required=True)
+    ap.add_argument("--workload", type=int, default=0)
     ap.add_argument("--trace", required=True)
     ap.add_argument("--fetch", help="omit both counter files to summarise the kernel trace only")
     ap.add_argument("--write")
@@ -59,7 +86,12 @@ def main() -> None:
                                                 "e.g. '--plan random-fit --scan'")
     ap.add_argument("--tag", default="", help="suffix of the summary's file name for such a run")
     ap.add_argument("--bench", required=True, help="the JSON line bench.py printed in the trace run")
+    ap.add_argument("--yardsticks", action="store_true",
+                    help="the trace is of `bench.py --yardsticks-only`: write profiles/bload_yardsticks_kernel_trace.md")
     args = ap.parse_args()
+    if args.yardsticks:
+        yardstick_summary(args)
+        return
     w = args.workload
     flags = (" " + args.flags.strip()) if args.flags.strip() else ""
     tag = ("_" + args.tag) if args.tag else ""
