@@ -484,26 +484,28 @@ struct RunCursor {
 };
 
 // A whole tile of kNarrowSlots slots that lies inside one run (`r`), or inside the padding
-// behind a block's last run (`r` null): four slots of the start table and, per step, one
-// 16-byte vector of payload per lane, without a look at any table.
-__device__ __forceinline__ void narrow_uniform_tile(const PackArgs& a, int64_t g0, const Run* r, bool payload)
+// behind a block's last run (`r` null): four slots of the start table (if `table`) and, per
+// step, one 16-byte vector of payload per lane (if `payload`), without a look at any table.
+__device__ __forceinline__ void narrow_uniform_tile(const PackArgs& a, int64_t g0, const Run* r, bool payload,
+                                                    bool table)
 {
     const int tid = (int)threadIdx.x;
-    const int64_t g = g0 + 4 * tid;
-    vec16 vs = {~0u, ~0u, ~0u, ~0u}, vf = vs;
-    uint32_t rs = 0, vl = 0;
-    if (r) {
-        const uint32_t fid = (uint32_t)(g - r->dst);               // >= 0: the run begins at or before the tile
-        vs = vec16{(uint32_t)r->seq, (uint32_t)r->seq, (uint32_t)r->seq, (uint32_t)r->seq};
-        vf = vec16{fid, fid + 1u, fid + 2u, fid + 3u};
-        rs = fid == 0u ? 1u : 0u;
-        vl = 0x01010101u;
+    if (table) {
+        const int64_t g = g0 + 4 * tid;
+        vec16 vs = {~0u, ~0u, ~0u, ~0u}, vf = vs;
+        uint32_t rs = 0, vl = 0;
+        if (r) {
+            const uint32_t fid = (uint32_t)(g - r->dst);           // >= 0: the run begins at or before the tile
+            vs = vec16{(uint32_t)r->seq, (uint32_t)r->seq, (uint32_t)r->seq, (uint32_t)r->seq};
+            vf = vec16{fid, fid + 1u, fid + 2u, fid + 3u};
+            rs = fid == 0u ? 1u : 0u;
+            vl = 0x01010101u;
+        }
+        store_stream(reinterpret_cast<vec16*>(a.seq_id + g), vs);
+        store_stream(reinterpret_cast<vec16*>(a.frame_idx + g), vf);
+        __builtin_nontemporal_store(rs, reinterpret_cast<uint32_t*>(a.reset + g));
+        __builtin_nontemporal_store(vl, reinterpret_cast<uint32_t*>(a.valid + g));
     }
-    store_stream(reinterpret_cast<vec16*>(a.seq_id + g), vs);
-    store_stream(reinterpret_cast<vec16*>(a.frame_idx + g), vf);
-    __builtin_nontemporal_store(rs, reinterpret_cast<uint32_t*>(a.reset + g));
-    __builtin_nontemporal_store(vl, reinterpret_cast<uint32_t*>(a.valid + g));
-
     if (!payload) return;
     const int64_t F = a.frame_bytes;
     vec16* dst = reinterpret_cast<vec16*>(a.packed + g0 * F);      // 16-byte aligned: g0 is a multiple of 1024
@@ -542,13 +544,18 @@ struct Assembled<vec16> {
 // FUSED (4-byte frames, e.g. tokens): the four slots of a lane's start-table
 // quad are also exactly one 16-byte vector of payload, so both are written in
 // the same pass and the payload pass is skipped.
-// PAYLOAD false: only the start table is written (the table pass of wide frames, whose payload
-// the 4 KiB tiles copy).
-template <typename E, bool FUSED, bool PAYLOAD = true>
+// PAYLOAD false: only the start table is written; TABLE false: only the payload.  Large tensors
+// of 4-byte frames are packed in two such passes, and the start table of large tensors of wide
+// frames, whose payload the 4 KiB tiles copy, by the first of them: five output streams written
+// at once reach 5.1-5.2 TB/s on this GPU, the payload alone 6.0 and the four planes of the table
+// alone 6.2 (plain streaming kernels with this traffic, 2^30 tokens: 3.46 ms in one pass, 1.17 +
+// 1.73 ms in two).
+template <typename E, bool FUSED, bool PAYLOAD = true, bool TABLE = true>
 __global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a, const Run* __restrict__ runs,
                                                                const int32_t* __restrict__ first_pos)
 {
-    static_assert(PAYLOAD || !FUSED, "the fused form writes the payload with the table");
+    static_assert(PAYLOAD || !FUSED, "the fused form is about the payload");
+    static_assert(PAYLOAD || TABLE, "a pass writes something");
     __shared__ RunTable<kNarrowMaxRuns> tab;
     const int tid = (int)threadIdx.x;
     const uint32_t tile = xcd_contiguous(blockIdx.x, gridDim.x);
@@ -565,16 +572,16 @@ __global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a, const
     if (nslot == kNarrowSlots && first < a.n_seq) {
         const Run r = runs[first];
         if (r.dst != kNoRun) {
-            if (r.dst <= g0 && r.dst + r.len >= g1) { narrow_uniform_tile(a, g0, &r, PAYLOAD); return; }
-            if (r.dst + r.len <= g0 && ((int64_t)r.block + 1) * a.t_blk >= g1) { narrow_uniform_tile(a, g0, nullptr, PAYLOAD); return; }
+            if (r.dst <= g0 && r.dst + r.len >= g1) { narrow_uniform_tile(a, g0, &r, PAYLOAD, TABLE); return; }
+            if (r.dst + r.len <= g0 && ((int64_t)r.block + 1) * a.t_blk >= g1) { narrow_uniform_tile(a, g0, nullptr, PAYLOAD, TABLE); return; }
         }
     }
 
     const int32_t last = (tile + 1 < gridDim.x) ? min(max(first_pos[tile + 1], 0), a.n_seq) : a.n_seq - 1;
     const int n = gather_runs(runs, a.n_seq, first, last, g0, g1, tab);
 
-    // start table: 4 consecutive slots per lane -> 16-byte / 4-byte stores
-    for (int q = tid; 4 * q < nslot; q += kThreads) {
+    // start table (and, FUSED, the payload): 4 consecutive slots per lane -> 16-byte / 4-byte stores
+    for (int q = tid; (TABLE || FUSED) && 4 * q < nslot; q += kThreads) {
         const int32_t s0 = 4 * q;
         RunCursor<kNarrowMaxRuns> cur(tab, n, s0);
         int32_t sid[4], fid[4];
@@ -602,6 +609,7 @@ __global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a, const
             }
             store_stream(reinterpret_cast<vec16*>(a.packed + (g0 + s0) * 4), pv);
         }
+        if (!TABLE) continue;
         const int64_t g = g0 + s0;
         if (s0 + 4 <= nslot) {
             const vec16 vs = {(uint32_t)sid[0], (uint32_t)sid[1], (uint32_t)sid[2], (uint32_t)sid[3]};
@@ -843,12 +851,26 @@ bload_status pack_enqueue(const PackLayout& l, const void* d_src, const int64_t*
         hipLaunchKernelGGL(pack_wide_kernel, grid, block, 0, stream, a, runs, first_pos, kWideTile, inv_unit,
                            l.table_tiles == 0 ? 1 : 0);
         if (l.table_tiles > 0)
-            hipLaunchKernelGGL((pack_narrow_kernel<uint8_t, false, false>), dim3((uint32_t)l.table_tiles), block, 0,
-                               stream, a, runs, first_pos_table);
-    } else if (frame_bytes % 16 == 0 && aligned_to(d_src, 16)) {
+            hipLaunchKernelGGL((pack_narrow_kernel<uint8_t, false, false, true>), dim3((uint32_t)l.table_tiles), block,
+                               0, stream, a, runs, first_pos_table);
+        return launch_status();
+    }
+    // slot tiles: one pass; 4-byte frames (whose payload and table share a loop, so that one kernel writes
+    // five streams at once) from kTablePassFromSlots slots on: the payload and the start table in a pass
+    // each over the same tiles.  Measured on 1.3 * 10^9 token slots: 3.98 -> 3.72 ms; frames of 6 and 8
+    // bytes, whose one pass already writes the table first and the payload after it, lose 5-7 % to the
+    // second pass's look-ups and keep the one pass.
+    if (frame_bytes % 16 == 0 && aligned_to(d_src, 16)) {
         hipLaunchKernelGGL((pack_narrow_kernel<vec16, false>), grid, block, 0, stream, a, runs, first_pos);
     } else if (frame_bytes == 4 && aligned_to(d_src, 4)) {
-        hipLaunchKernelGGL((pack_narrow_kernel<uint32_t, true>), grid, block, 0, stream, a, runs, first_pos);
+        if (a.total_slots >= kTablePassFromSlots) {
+            hipLaunchKernelGGL((pack_narrow_kernel<uint32_t, true, true, false>), grid, block, 0, stream, a, runs,
+                               first_pos);
+            hipLaunchKernelGGL((pack_narrow_kernel<uint8_t, false, false, true>), grid, block, 0, stream, a, runs,
+                               first_pos);
+        } else {
+            hipLaunchKernelGGL((pack_narrow_kernel<uint32_t, true>), grid, block, 0, stream, a, runs, first_pos);
+        }
     } else if (frame_bytes % 4 == 0 && aligned_to(d_src, 4)) {
         hipLaunchKernelGGL((pack_narrow_kernel<uint32_t, false>), grid, block, 0, stream, a, runs, first_pos);
     } else if (frame_bytes % 2 == 0 && aligned_to(d_src, 2)) {

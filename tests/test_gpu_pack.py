@@ -162,3 +162,27 @@ def test_pack_large_tensors_of_wide_frames(n, T, F, kind, progress):
     torch.cuda.synchronize()
     assert_packed_equal_whole(out, src, so, L, ref_plan, F, max(1, (64 << 20) // (T * F)),
                               f"n={n} T={T} F={F} {kind}: ", say=progress)
+
+
+@pytest.mark.parametrize("n,T,F,kind", [(400000, 256, 4, "mixed"),     # tokens: payload and table share a quad per lane
+                                        (300000, 100, 6, "uniform"),   # 2-byte elements
+                                        (500000, 33, 12, "uniform"),   # 4-byte elements, blocks not a multiple of anything
+                                        (100000, 300, 48, "mixed"),    # 16-byte vectors
+                                        (2500000, 7, 1, "short")])     # bytes, blocks far shorter than a tile
+def test_pack_large_tensors_of_small_frames(n, T, F, kind, progress):
+    """Large tensors in slot tiles (from 2^21 slots on, 4-byte frames are written in two passes,
+    payload and start table): every block against the oracle, slab by slab."""
+    from gpu_util import assert_packed_equal_whole
+    bl = binding()
+    rng = np.random.default_rng(n + T + F)
+    L = workloads.random_lengths(rng, n, T, kind)
+    so = workloads.src_offsets(L)
+    src = rng.integers(0, 256, size=int(so[-1]) * F, dtype=np.uint8)
+    ref_plan = oracle.plan(L, T, oracle.order(n, 3))
+    assert ref_plan.num_blocks * T >= 1 << 21
+    assert bl.bload_pack_tile_bytes(n, ref_plan.num_blocks, T, F, True) == 0
+    plan_dev = upload_plan(ref_plan, n)
+    out = bl.bload_pack(to_dev(src), to_dev(so), to_dev(L), plan_dev, F)
+    torch.cuda.synchronize()
+    assert_packed_equal_whole(out, src, so, L, ref_plan, F, max(1, (64 << 20) // (T * F)),
+                              f"n={n} T={T} F={F} {kind}: ", say=progress)
