@@ -483,30 +483,33 @@ struct RunCursor {
     }
 };
 
-// A whole tile of kNarrowSlots slots that lies inside one run (`r`), or inside the padding
-// behind a block's last run (`r` null): four slots of the start table (if `table`) and, per
-// step, one 16-byte vector of payload per lane (if `payload`), without a look at any table.
-__device__ __forceinline__ void narrow_uniform_tile(const PackArgs& a, int64_t g0, const Run* r, bool payload,
-                                                    bool table)
+// What a tile of kNarrowSlots slots is, as far as the run its entry names can tell.
+enum NarrowKind : int { kTileGeneral = 0, kTileOneRun = 1, kTilePadding = 2, kTileAbsent = 3 };
+
+// The start-table entries of a whole tile that lies inside one run (`r`), or inside the padding
+// behind a block's last run (`r` null): four slots per lane, without a look at any table.
+__device__ __forceinline__ void narrow_uniform_table(const PackArgs& a, int64_t g0, const Run* r)
+{
+    const int64_t g = g0 + 4 * (int)threadIdx.x;
+    vec16 vs = {~0u, ~0u, ~0u, ~0u}, vf = vs;
+    uint32_t rs = 0, vl = 0;
+    if (r) {
+        const uint32_t fid = (uint32_t)(g - r->dst);           // >= 0: the run begins at or before the tile
+        vs = vec16{(uint32_t)r->seq, (uint32_t)r->seq, (uint32_t)r->seq, (uint32_t)r->seq};
+        vf = vec16{fid, fid + 1u, fid + 2u, fid + 3u};
+        rs = fid == 0u ? 1u : 0u;
+        vl = 0x01010101u;
+    }
+    store_stream(reinterpret_cast<vec16*>(a.seq_id + g), vs);
+    store_stream(reinterpret_cast<vec16*>(a.frame_idx + g), vf);
+    __builtin_nontemporal_store(rs, reinterpret_cast<uint32_t*>(a.reset + g));
+    __builtin_nontemporal_store(vl, reinterpret_cast<uint32_t*>(a.valid + g));
+}
+
+// The payload of such a tile: per step one 16-byte vector per lane.
+__device__ __forceinline__ void narrow_uniform_payload(const PackArgs& a, int64_t g0, const Run* r)
 {
     const int tid = (int)threadIdx.x;
-    if (table) {
-        const int64_t g = g0 + 4 * tid;
-        vec16 vs = {~0u, ~0u, ~0u, ~0u}, vf = vs;
-        uint32_t rs = 0, vl = 0;
-        if (r) {
-            const uint32_t fid = (uint32_t)(g - r->dst);           // >= 0: the run begins at or before the tile
-            vs = vec16{(uint32_t)r->seq, (uint32_t)r->seq, (uint32_t)r->seq, (uint32_t)r->seq};
-            vf = vec16{fid, fid + 1u, fid + 2u, fid + 3u};
-            rs = fid == 0u ? 1u : 0u;
-            vl = 0x01010101u;
-        }
-        store_stream(reinterpret_cast<vec16*>(a.seq_id + g), vs);
-        store_stream(reinterpret_cast<vec16*>(a.frame_idx + g), vf);
-        __builtin_nontemporal_store(rs, reinterpret_cast<uint32_t*>(a.reset + g));
-        __builtin_nontemporal_store(vl, reinterpret_cast<uint32_t*>(a.valid + g));
-    }
-    if (!payload) return;
     const int64_t F = a.frame_bytes;
     vec16* dst = reinterpret_cast<vec16*>(a.packed + g0 * F);      // 16-byte aligned: g0 is a multiple of 1024
     const int32_t nvec = (int32_t)(kNarrowSlots * F / 16);
@@ -541,43 +544,16 @@ struct Assembled<vec16> {
     __device__ __forceinline__ vec16 get(int) const { return vec; }
 };
 
-// FUSED (4-byte frames, e.g. tokens): the four slots of a lane's start-table
-// quad are also exactly one 16-byte vector of payload, so both are written in
-// the same pass and the payload pass is skipped.
-// PAYLOAD false: only the start table is written; TABLE false: only the payload.  Large tensors
-// of 4-byte frames are packed in two such passes, and the start table of large tensors of wide
-// frames, whose payload the 4 KiB tiles copy, by the first of them: five output streams written
-// at once reach 5.1-5.2 TB/s on this GPU, the payload alone 6.0 and the four planes of the table
-// alone 6.2 (plain streaming kernels with this traffic, 2^30 tokens: 3.46 ms in one pass, 1.17 +
-// 1.73 ms in two).
-template <typename E, bool FUSED, bool PAYLOAD = true, bool TABLE = true>
-__global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a, const Run* __restrict__ runs,
-                                                               const int32_t* __restrict__ first_pos)
+// One tile of kNarrowSlots slots (or the shorter last one) that needs its runs looked up: the
+// candidates `first` .. `last` of the run table are gathered into `tab` first.  Called by the
+// whole workgroup.
+template <typename E, bool FUSED, bool PAYLOAD, bool TABLE>
+__device__ __forceinline__ void narrow_general_tile(const PackArgs& a, const Run* __restrict__ runs,
+                                                    RunTable<kNarrowMaxRuns>& tab, int64_t g0, int64_t g1,
+                                                    int32_t first, int32_t last)
 {
-    static_assert(PAYLOAD || !FUSED, "the fused form is about the payload");
-    static_assert(PAYLOAD || TABLE, "a pass writes something");
-    __shared__ RunTable<kNarrowMaxRuns> tab;
     const int tid = (int)threadIdx.x;
-    const uint32_t tile = xcd_contiguous(blockIdx.x, gridDim.x);
-    const int64_t g0 = (int64_t)tile * kNarrowSlots;
-    const int64_t g1 = min(g0 + kNarrowSlots, a.total_slots);
     const int nslot = (int)(g1 - g0);
-    const int32_t first = min(max(first_pos[tile], 0), a.n_seq);
-
-    // The two most common tiles where sequences are long need no table: a tile inside one run,
-    // and a tile inside the padding behind its block's last run.  The tile's entry names the
-    // last run of the tile's first block that begins at or before the tile; that record alone
-    // tells (runs of a block follow each other without a gap).  Two wave-uniform look-ups, no
-    // LDS, no barrier: every wave decides alone and all decide alike.
-    if (nslot == kNarrowSlots && first < a.n_seq) {
-        const Run r = runs[first];
-        if (r.dst != kNoRun) {
-            if (r.dst <= g0 && r.dst + r.len >= g1) { narrow_uniform_tile(a, g0, &r, PAYLOAD, TABLE); return; }
-            if (r.dst + r.len <= g0 && ((int64_t)r.block + 1) * a.t_blk >= g1) { narrow_uniform_tile(a, g0, nullptr, PAYLOAD, TABLE); return; }
-        }
-    }
-
-    const int32_t last = (tile + 1 < gridDim.x) ? min(max(first_pos[tile + 1], 0), a.n_seq) : a.n_seq - 1;
     const int n = gather_runs(runs, a.n_seq, first, last, g0, g1, tab);
 
     // start table (and, FUSED, the payload): 4 consecutive slots per lane -> 16-byte / 4-byte stores
@@ -665,6 +641,112 @@ __global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a, const
             for (int e = 0; e < EPV; ++e)
                 if (e < nvalid) reinterpret_cast<E*>(dst_tile)[w + e] = u.get(e);
         }
+    }
+}
+
+// FUSED (4-byte frames, e.g. tokens): the four slots of a lane's start-table
+// quad are also exactly one 16-byte vector of payload, so both are written in
+// the same pass and the payload pass is skipped.
+// PAYLOAD false: only the start table is written; TABLE false: only the payload.  Large tensors
+// of 4-byte frames are packed in two such passes, and the start table of large tensors of wide
+// frames, whose payload the 4 KiB tiles copy, by the first of them: five output streams written
+// at once reach 5.1-5.2 TB/s on this GPU, the payload alone 6.0 and the four planes of the table
+// alone 6.2 (plain streaming kernels with this traffic, 2^30 tokens: 3.46 ms in one pass, 1.17 +
+// 1.73 ms in two).
+// GROUP consecutive tiles per workgroup.  What decides a tile's kind hangs on two look-ups, one
+// after the other (the tile's entry, then the run it names), and the payload on a third: with
+// several tiles per workgroup the look-ups of a stage are asked for together, and so is the
+// payload of all tiles that lie inside one run, so that a wave has GROUP times the bytes in
+// flight per wait.  Tiles that need their runs gathered follow one by one.
+template <typename E, bool FUSED, bool PAYLOAD = true, bool TABLE = true, int GROUP = 1>
+__global__ __launch_bounds__(kThreads) void pack_narrow_kernel(PackArgs a, const Run* __restrict__ runs,
+                                                               const int32_t* __restrict__ first_pos,
+                                                               uint32_t n_tiles)
+{
+    static_assert(PAYLOAD || !FUSED, "the fused form is about the payload");
+    static_assert(PAYLOAD || TABLE, "a pass writes something");
+    __shared__ RunTable<kNarrowMaxRuns> tab;
+    const int tid = (int)threadIdx.x;
+    const uint32_t tile0 = xcd_contiguous(blockIdx.x, gridDim.x) * (uint32_t)GROUP;
+
+    // entry[u]: where tile tile0 + u starts in the run table; behind the last tile: the last run
+    int32_t entry[GROUP + 1];
+#pragma unroll
+    for (int u = 0; u <= GROUP; ++u) {
+        const uint32_t t = tile0 + (uint32_t)u;
+        entry[u] = first_pos[min(t, n_tiles - 1u)];
+    }
+#pragma unroll
+    for (int u = 0; u <= GROUP; ++u)
+        entry[u] = tile0 + (uint32_t)u < n_tiles ? min(max(entry[u], 0), a.n_seq) : a.n_seq - 1;
+
+    // The two most common tiles where sequences are long need no table: a tile inside one run,
+    // and a tile inside the padding behind its block's last run.  The tile's entry names the
+    // last run of the tile's first block that begins at or before the tile; that record alone
+    // tells (runs of a block follow each other without a gap).  Wave-uniform look-ups, no LDS,
+    // no barrier: every wave decides alone and all decide alike.
+    Run r[GROUP];
+#pragma unroll
+    for (int u = 0; u < GROUP; ++u) r[u] = runs[min(entry[u], a.n_seq - 1)];
+    int kind[GROUP];
+#pragma unroll
+    for (int u = 0; u < GROUP; ++u) {
+        const uint32_t t = tile0 + (uint32_t)u;
+        const int64_t g0 = (int64_t)t * kNarrowSlots, g1 = g0 + kNarrowSlots;
+        kind[u] = kTileGeneral;
+        if (t >= n_tiles) {
+            kind[u] = kTileAbsent;
+        } else if (g1 <= a.total_slots && entry[u] < a.n_seq && r[u].dst != kNoRun) {
+            if (r[u].dst <= g0 && r[u].dst + r[u].len >= g1) kind[u] = kTileOneRun;
+            else if (r[u].dst + r[u].len <= g0 && ((int64_t)r[u].block + 1) * a.t_blk >= g1) kind[u] = kTilePadding;
+        }
+    }
+
+    if (PAYLOAD && FUSED) {
+        // 4-byte frames: a tile's payload is one 16-byte vector per lane
+        vec16 pv[GROUP];
+#pragma unroll
+        for (int u = 0; u < GROUP; ++u) {
+            pv[u] = vec16{0u, 0u, 0u, 0u};
+            if (kind[u] == kTileOneRun) {
+                const int64_t g0 = (int64_t)(tile0 + (uint32_t)u) * kNarrowSlots;
+                const uint8_t* from = a.src + (r[u].src + (g0 - r[u].dst)) * 4;
+                pv[u] = __builtin_nontemporal_load(reinterpret_cast<const vec16_unaligned*>(from) + tid);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < GROUP; ++u) {
+            if (kind[u] == kTileOneRun || kind[u] == kTilePadding) {
+                const int64_t g0 = (int64_t)(tile0 + (uint32_t)u) * kNarrowSlots;
+                store_stream(reinterpret_cast<vec16*>(a.packed + g0 * 4) + tid, pv[u]);
+            }
+        }
+    } else if (PAYLOAD) {
+#pragma unroll
+        for (int u = 0; u < GROUP; ++u) {
+            const int64_t g0 = (int64_t)(tile0 + (uint32_t)u) * kNarrowSlots;
+            if (kind[u] == kTileOneRun) narrow_uniform_payload(a, g0, &r[u]);
+            else if (kind[u] == kTilePadding) narrow_uniform_payload(a, g0, nullptr);
+        }
+    }
+    if (TABLE) {
+#pragma unroll
+        for (int u = 0; u < GROUP; ++u) {
+            const int64_t g0 = (int64_t)(tile0 + (uint32_t)u) * kNarrowSlots;
+            if (kind[u] == kTileOneRun) narrow_uniform_table(a, g0, &r[u]);
+            else if (kind[u] == kTilePadding) narrow_uniform_table(a, g0, nullptr);
+        }
+    }
+
+    bool table_in_use = false;
+#pragma unroll
+    for (int u = 0; u < GROUP; ++u) {
+        if (kind[u] != kTileGeneral) continue;
+        const int64_t g0 = (int64_t)(tile0 + (uint32_t)u) * kNarrowSlots;
+        if (table_in_use) __syncthreads();           // the tile before is done with the gathered runs
+        narrow_general_tile<E, FUSED, PAYLOAD, TABLE>(a, runs, tab, g0, min(g0 + kNarrowSlots, a.total_slots),
+                                                      entry[u], entry[u + 1]);
+        table_in_use = true;
     }
 }
 
@@ -762,6 +844,10 @@ struct PackLayout {
 // without them, 9.36 ms with the pass).  About 3 ns per 1000 slots: below a couple of million
 // slots the pass saves less than its launch costs, and the one pass stays.
 constexpr int64_t kTablePassFromSlots = (int64_t)1 << 21;
+// Tiles per workgroup in the passes that large tensors get (pack_narrow_kernel's GROUP).  Measured on
+// 0.8-1.3 * 10^9 token slots of four length mixes: two tiles 1-3.5 % faster than one, four between 3 %
+// slower and 2 % faster, eight 40 % slower.
+constexpr int kPassGroup = 2;
 
 // Sizes the caller cannot know in advance (which tile shape the lengths will choose) are
 // taken at their larger value when `for_query`.
@@ -847,12 +933,14 @@ bload_status pack_enqueue(const PackLayout& l, const void* d_src, const int64_t*
                        d_offset_of_seq, d_block_first, (int32_t)n_seq, num_blocks, (int64_t)t_blk, unit_bytes,
                        l.tiles, tile_units, inv_unit, inv_t, runs, first_pos, l.table_tiles, first_pos_table);
     const dim3 grid((uint32_t)l.tiles), block(kThreads);
+    const uint32_t n_tiles = (uint32_t)l.tiles;
     if (l.wide) {
         hipLaunchKernelGGL(pack_wide_kernel, grid, block, 0, stream, a, runs, first_pos, kWideTile, inv_unit,
                            l.table_tiles == 0 ? 1 : 0);
         if (l.table_tiles > 0)
-            hipLaunchKernelGGL((pack_narrow_kernel<uint8_t, false, false, true>), dim3((uint32_t)l.table_tiles), block,
-                               0, stream, a, runs, first_pos_table);
+            hipLaunchKernelGGL((pack_narrow_kernel<uint8_t, false, false, true, kPassGroup>),
+                               dim3((uint32_t)ceil_div(l.table_tiles, kPassGroup)), block, 0, stream, a, runs,
+                               first_pos_table, (uint32_t)l.table_tiles);
         return launch_status();
     }
     // slot tiles: one pass; 4-byte frames (whose payload and table share a loop, so that one kernel writes
@@ -861,22 +949,23 @@ bload_status pack_enqueue(const PackLayout& l, const void* d_src, const int64_t*
     // bytes, whose one pass already writes the table first and the payload after it, lose 5-7 % to the
     // second pass's look-ups and keep the one pass.
     if (frame_bytes % 16 == 0 && aligned_to(d_src, 16)) {
-        hipLaunchKernelGGL((pack_narrow_kernel<vec16, false>), grid, block, 0, stream, a, runs, first_pos);
+        hipLaunchKernelGGL((pack_narrow_kernel<vec16, false>), grid, block, 0, stream, a, runs, first_pos, n_tiles);
     } else if (frame_bytes == 4 && aligned_to(d_src, 4)) {
         if (a.total_slots >= kTablePassFromSlots) {
-            hipLaunchKernelGGL((pack_narrow_kernel<uint32_t, true, true, false>), grid, block, 0, stream, a, runs,
-                               first_pos);
-            hipLaunchKernelGGL((pack_narrow_kernel<uint8_t, false, false, true>), grid, block, 0, stream, a, runs,
-                               first_pos);
+            const dim3 groups((uint32_t)ceil_div(l.tiles, kPassGroup));
+            hipLaunchKernelGGL((pack_narrow_kernel<uint32_t, true, true, false, kPassGroup>), groups, block, 0, stream,
+                               a, runs, first_pos, n_tiles);
+            hipLaunchKernelGGL((pack_narrow_kernel<uint8_t, false, false, true, kPassGroup>), groups, block, 0, stream,
+                               a, runs, first_pos, n_tiles);
         } else {
-            hipLaunchKernelGGL((pack_narrow_kernel<uint32_t, true>), grid, block, 0, stream, a, runs, first_pos);
+            hipLaunchKernelGGL((pack_narrow_kernel<uint32_t, true>), grid, block, 0, stream, a, runs, first_pos, n_tiles);
         }
     } else if (frame_bytes % 4 == 0 && aligned_to(d_src, 4)) {
-        hipLaunchKernelGGL((pack_narrow_kernel<uint32_t, false>), grid, block, 0, stream, a, runs, first_pos);
+        hipLaunchKernelGGL((pack_narrow_kernel<uint32_t, false>), grid, block, 0, stream, a, runs, first_pos, n_tiles);
     } else if (frame_bytes % 2 == 0 && aligned_to(d_src, 2)) {
-        hipLaunchKernelGGL((pack_narrow_kernel<uint16_t, false>), grid, block, 0, stream, a, runs, first_pos);
+        hipLaunchKernelGGL((pack_narrow_kernel<uint16_t, false>), grid, block, 0, stream, a, runs, first_pos, n_tiles);
     } else {
-        hipLaunchKernelGGL((pack_narrow_kernel<uint8_t, false>), grid, block, 0, stream, a, runs, first_pos);
+        hipLaunchKernelGGL((pack_narrow_kernel<uint8_t, false>), grid, block, 0, stream, a, runs, first_pos, n_tiles);
     }
     return launch_status();
 }

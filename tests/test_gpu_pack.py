@@ -165,6 +165,9 @@ def test_pack_large_tensors_of_wide_frames(n, T, F, kind, progress):
 
 
 @pytest.mark.parametrize("n,T,F,kind", [(400000, 256, 4, "mixed"),     # tokens: payload and table share a quad per lane
+                                        (3000, 4096, 4, "long"),       # tokens: most tiles inside one run or inside padding
+                                        (5000, 3000, 4, "mixed"),      # tokens: blocks that are no whole number of tiles
+                                        (2052, 1025, 4, "long"),       # tokens: an odd number of tiles, the last one short
                                         (300000, 100, 6, "uniform"),   # 2-byte elements
                                         (500000, 33, 12, "uniform"),   # 4-byte elements, blocks not a multiple of anything
                                         (100000, 300, 48, "mixed"),    # 16-byte vectors
