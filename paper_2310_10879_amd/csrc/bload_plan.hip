@@ -17,7 +17,9 @@
 // jumping round: every tile jumps inside its own LDS until each of its positions
 // has left the tile (exit[p]); one thread follows exit[] from position 0 and
 // notes where the orbit enters each tile (one hop per tile); every tile then
-// marks its heads from its entry by jumping in LDS again.  Seven launches at any size.
+// marks its heads from its entry by jumping in LDS again.  Seven launches at any size; five
+// up to 8192 sequences, where the one tile is entered at position 0 and the first two of the
+// three steps fall away.
 #include "bload_common.hpp"
 #include "bload_order.hpp"
 
@@ -266,8 +268,8 @@ __global__ __launch_bounds__(kThreads) void plan_chain_kernel(const int32_t* __r
     }
 }
 
-// The heads inside a jump tile, from the position where the orbit enters it: pointer jumping
-// with marks in LDS.  Also, for each of its scan tiles (one per wave), the number of heads
+// The heads inside a jump tile, from the position where the orbit enters it (`tile_entry` null:
+// there is one tile only, entered at position 0): pointer jumping with marks in LDS.  Also, for each of its scan tiles (one per wave), the number of heads
 // and the last head.
 __global__ __launch_bounds__(kJumpThreads) void plan_mark_kernel(
     const int32_t* __restrict__ next, const int32_t* __restrict__ tile_entry, int32_t n_seq,
@@ -278,7 +280,7 @@ __global__ __launch_bounds__(kJumpThreads) void plan_mark_kernel(
     __shared__ HeadPair s_wave[kJumpThreads / kWave];
     const int32_t lo = (int32_t)blockIdx.x * kJumpTile;
     const int32_t count = min(kJumpTile, n_seq - lo);
-    const int32_t entry = tile_entry[blockIdx.x];
+    const int32_t entry = tile_entry ? tile_entry[blockIdx.x] : 0;
     copy_tile<kJumpThreads>(next + lo, s_jump[0], count);
     for (int32_t k = (int32_t)threadIdx.x; k < count; k += kJumpThreads) s_mark[k] = (uint8_t)(lo + k == entry);
     if (entry >= 0) {
@@ -557,11 +559,15 @@ extern "C" bload_status bload_plan(const int32_t* d_lengths, int64_t n_seq, int3
                            prefix);
         hipLaunchKernelGGL(plan_next_kernel, dim3((uint32_t)ceil_div(n_seq, kThreads)), block, 0, stream,
                            prefix, n, t_blk, next);
-        hipLaunchKernelGGL(plan_exit_kernel, jump_tiles, dim3(kJumpThreads), 0, stream, next, n, exit_of);
-        hipLaunchKernelGGL(plan_chain_kernel, dim3(1), block, 0, stream, exit_of, n, l.n_jump_tiles,
-                           tile_entry);
-        hipLaunchKernelGGL(plan_mark_kernel, jump_tiles, dim3(kJumpThreads), 0, stream, next, tile_entry, n, mark,
-                           tile_cnt, tile_head);
+        // where the orbit of position 0 enters each jump tile; a single tile it enters at 0
+        const bool one_jump_tile = l.n_jump_tiles == 1;
+        if (!one_jump_tile) {
+            hipLaunchKernelGGL(plan_exit_kernel, jump_tiles, dim3(kJumpThreads), 0, stream, next, n, exit_of);
+            hipLaunchKernelGGL(plan_chain_kernel, dim3(1), block, 0, stream, exit_of, n, l.n_jump_tiles,
+                               tile_entry);
+        }
+        hipLaunchKernelGGL(plan_mark_kernel, jump_tiles, dim3(kJumpThreads), 0, stream, next,
+                           one_jump_tile ? nullptr : tile_entry, n, mark, tile_cnt, tile_head);
         hipLaunchKernelGGL(plan_assign_kernel, tiles, block, 0, stream, mark, d_order, prefix, n,
                            tile_cnt, tile_head, tile_bad, d_block_of_seq, d_offset_of_seq,
                            d_block_first, result);
