@@ -269,7 +269,12 @@ __global__ __launch_bounds__(kThreads) void plan_chain_kernel(const int32_t* __r
 }
 
 // The heads inside a jump tile, from the position where the orbit enters it (`tile_entry` null:
-// there is one tile only, entered at position 0): pointer jumping with marks in LDS.  Also, for each of its scan tiles (one per wave), the number of heads
+// there is one tile only, entered at position 0).  The heads found so far are kept as a list in
+// orbit order, h_0 = the entry: round r jumps every position of the tile from next^(2^r) to
+// next^(2^(r+1)) as the exit kernel does, and before that the first 2^r heads look up theirs,
+// which are h_(2^r) .. h_(2^(r+1) - 1) where those still lie inside the tile (an orbit only
+// moves forward, so they leave the tile in order and the list has no holes).  A round that
+// adds no head ends the search.  Also, for each of its scan tiles (one per wave), the number of heads
 // and the last head.
 __global__ __launch_bounds__(kJumpThreads) void plan_mark_kernel(
     const int32_t* __restrict__ next, const int32_t* __restrict__ tile_entry, int32_t n_seq,
@@ -277,19 +282,46 @@ __global__ __launch_bounds__(kJumpThreads) void plan_mark_kernel(
 {
     __shared__ int32_t s_jump[2][kJumpTile];
     __shared__ __attribute__((aligned(16))) uint8_t s_mark[kJumpTile];
+    __shared__ uint16_t s_heads[kJumpTile];           // positions inside the tile, relative to its first
+    __shared__ int32_t s_n_heads;
     __shared__ HeadPair s_wave[kJumpThreads / kWave];
+    static_assert(kJumpTile <= 65536, "a head's place inside the tile is kept in 16 bits");
     const int32_t lo = (int32_t)blockIdx.x * kJumpTile;
     const int32_t count = min(kJumpTile, n_seq - lo);
     const int32_t entry = tile_entry ? tile_entry[blockIdx.x] : 0;
     copy_tile<kJumpThreads>(next + lo, s_jump[0], count);
     for (int32_t k = (int32_t)threadIdx.x; k < count; k += kJumpThreads) s_mark[k] = (uint8_t)(lo + k == entry);
-    if (entry >= 0) {
+    if (threadIdx.x == 0) {
+        s_heads[0] = (uint16_t)max(entry - lo, 0);
+        s_n_heads = entry >= 0 ? 1 : 0;
+    }
+    __syncthreads();
+    int32_t n_heads = entry >= 0 ? 1 : 0;            // the same in every thread
+    if (n_heads > 0) {
         int cur = 0;
         for (int r = 0; r < kJumpRounds; ++r) {
-            __syncthreads();
-            const bool more = jump_round<true, kJumpThreads>(s_jump[cur], s_jump[cur ^ 1], s_mark, lo, count);
+            const int32_t* jump = s_jump[cur];
+            for (int32_t i0 = (int32_t)threadIdx.x - lane_id(); i0 < n_heads; i0 += kJumpThreads) {   // wave-uniform
+                const int32_t i = i0 + lane_id();
+                const int32_t to = i < n_heads ? jump[s_heads[i]] - lo : count;
+                const bool inside = to < count;
+                if (inside) {
+                    s_heads[n_heads + i] = (uint16_t)to;
+                    s_mark[to] = 1;
+                }
+                // the new heads of a round are the first so many of its candidates: the last lane
+                // that found one speaks for its wave
+                const unsigned long long found = __ballot(inside);
+                if (found != 0ull && lane_id() == 63 - __builtin_clzll(found)) atomicMax(&s_n_heads, n_heads + i + 1);
+            }
+            const bool more = jump_round<false, kJumpThreads>(s_jump[cur], s_jump[cur ^ 1], nullptr, lo, count);
             cur ^= 1;
-            if (!__syncthreads_or(more ? 1 : 0)) break;
+            const bool any_inside = __syncthreads_or(more ? 1 : 0) != 0;
+            const int32_t now = s_n_heads;
+            const bool grew = now > n_heads;
+            n_heads = now;
+            if (!grew || !any_inside) break;
+            __syncthreads();                          // everyone has read s_n_heads before the next round updates it
         }
     }
     __syncthreads();
