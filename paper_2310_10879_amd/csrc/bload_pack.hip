@@ -647,12 +647,14 @@ __device__ __forceinline__ void narrow_general_tile(const PackArgs& a, const Run
 // FUSED (4-byte frames, e.g. tokens): the four slots of a lane's start-table
 // quad are also exactly one 16-byte vector of payload, so both are written in
 // the same pass and the payload pass is skipped.
+//
 // PAYLOAD false: only the start table is written; TABLE false: only the payload.  Large tensors
 // of 4-byte frames are packed in two such passes, and the start table of large tensors of wide
 // frames, whose payload the 4 KiB tiles copy, by the first of them: five output streams written
 // at once reach 5.1-5.2 TB/s on this GPU, the payload alone 6.0 and the four planes of the table
 // alone 6.2 (plain streaming kernels with this traffic, 2^30 tokens: 3.46 ms in one pass, 1.17 +
 // 1.73 ms in two).
+//
 // GROUP consecutive tiles per workgroup.  What decides a tile's kind hangs on two look-ups, one
 // after the other (the tile's entry, then the run it names), and the payload on a third: with
 // several tiles per workgroup the look-ups of a stage are asked for together, and so is the
