@@ -64,7 +64,9 @@ def test_workspace_queries(lib):
     tiles = 324084 * 2                             # blocks of 5000 token slots are cut into two tiles each:
     assert f(324084, 5000, 1, 3) == tiles * 16 + 2 * (-(-tiles * 8 // 16) * 16)   # a descriptor and two int64 partials per tile
     assert f(324084, 4096, 1, 3) == 0 and f(5, 2048, 1, 3) == 0 and f(9, 33, 1, 3) == 0   # tiles of whole blocks cut nothing
-    assert f(34576, 3000, 80, 2) == 0              # one chunk per block
+    assert f(10000, 3000, 80, 2) == 0              # one chunk per block
+    chunks = 34576 * 3                             # few long rounds of whole blocks: three chunks per block
+    assert f(34576, 3000, 80, 2) == chunks * 16 + 2 * chunks * 80 * 4
     assert f(180, 600, 37632, 0) == 0              # enough blocks x lane-slices: one chunk per block
     assert f(79, 3000, 2048, 1) > 0                # few blocks: cut in time, partial sums needed
     assert f(0, 600, 8, 0) == 0 and f(5, 0, 8, 0) == 0 and f(5, 8, 8, 7) == 0
