@@ -36,8 +36,10 @@ def test_plan_workloads_full_size(wid):
         assert_plan_equal(gpu_plan(L, w.t_blk, seed), ref, w.n_seq)
 
 
-def test_plan_closed_forms():
-    n, T = 4100, 12
+@pytest.mark.parametrize("n", [4100, 8192, 20000])        # one jump tile, a full one, three
+def test_plan_closed_forms(n):
+    # every position a block head; one block head in 12; every position; every second one
+    T = 12
     for L in (np.full(n, T), np.ones(n), np.full(n, T // 2 + 1), np.full(n, T // 2)):
         L = L.astype(np.int32)
         ref = oracle.plan(L, T, oracle.order(n, 5))
