@@ -143,6 +143,42 @@ __device__ __forceinline__ bool jump_round(const int32_t* __restrict__ from, int
     return inside_any;
 }
 
+// The same round (without marks) over a whole jump tile of kJumpTile positions, four neighbouring
+// positions per thread and step: their pointers come and go as one 16-byte LDS access, only the
+// look-ups behind them are single words (24 LDS instructions per thread and round instead of
+// 48).  Positions from `count` on must hold pointers that point behind the tile.
+__device__ __forceinline__ bool jump_round_tile(const int32_t* __restrict__ from, int32_t* __restrict__ to,
+                                                int32_t lo, int32_t count)
+{
+    typedef int32_t int4v __attribute__((ext_vector_type(4)));
+    constexpr int kQuads = kJumpTile / 4 / kJumpThreads;      // quads of positions per thread
+    static_assert(kQuads * 4 * kJumpThreads == kJumpTile, "the threads' quads tile the jump tile");
+    int4v at[kQuads], then[kQuads];
+#pragma unroll
+    for (int u = 0; u < kQuads; ++u)
+        at[u] = *reinterpret_cast<const int4v*>(from + 4 * ((int)threadIdx.x + u * kJumpThreads));
+    bool inside_any = false;
+#pragma unroll
+    for (int u = 0; u < kQuads; ++u) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool inside = at[u][j] - lo < count;
+            inside_any |= inside;
+            then[u][j] = inside ? from[at[u][j] - lo] : at[u][j];
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kQuads; ++u)
+        *reinterpret_cast<int4v*>(to + 4 * ((int)threadIdx.x + u * kJumpThreads)) = then[u];
+    return inside_any;
+}
+
+// Pointers behind the tile for the positions of a jump tile that lie behind the last sequence.
+__device__ __forceinline__ void pad_tile(int32_t* tile, int32_t lo, int32_t count)
+{
+    for (int32_t k = count + (int32_t)threadIdx.x; k < kJumpTile; k += kJumpThreads) tile[k] = lo + count;
+}
+
 // ---- kernels ------------------------------------------------------------------
 
 // order[p], the shuffled lengths, and per tile: the sum of its lengths, and whether one of them
@@ -236,14 +272,15 @@ __global__ __launch_bounds__(kJumpThreads) void plan_exit_kernel(const int32_t* 
                                                                  int32_t n_seq,
                                                                  int32_t* __restrict__ exit_of)
 {
-    __shared__ int32_t s_jump[2][kJumpTile];
+    __shared__ __attribute__((aligned(16))) int32_t s_jump[2][kJumpTile];
     const int32_t lo = (int32_t)blockIdx.x * kJumpTile;
     const int32_t count = min(kJumpTile, n_seq - lo);
     copy_tile<kJumpThreads>(next + lo, s_jump[0], count);
+    pad_tile(s_jump[0], lo, count);
     int cur = 0;
     for (int r = 0; r < kJumpRounds; ++r) {
         __syncthreads();
-        const bool more = jump_round<false, kJumpThreads>(s_jump[cur], s_jump[cur ^ 1], nullptr, lo, count);
+        const bool more = jump_round_tile(s_jump[cur], s_jump[cur ^ 1], lo, count);
         cur ^= 1;
         if (!__syncthreads_or(more ? 1 : 0)) break;       // every pointer has left the tile
     }
@@ -280,7 +317,7 @@ __global__ __launch_bounds__(kJumpThreads) void plan_mark_kernel(
     const int32_t* __restrict__ next, const int32_t* __restrict__ tile_entry, int32_t n_seq,
     uint8_t* __restrict__ mark, int32_t* __restrict__ tile_cnt, int32_t* __restrict__ tile_head)
 {
-    __shared__ int32_t s_jump[2][kJumpTile];
+    __shared__ __attribute__((aligned(16))) int32_t s_jump[2][kJumpTile];
     __shared__ __attribute__((aligned(16))) uint8_t s_mark[kJumpTile];
     __shared__ uint16_t s_heads[kJumpTile];           // positions inside the tile, relative to its first
     __shared__ int32_t s_n_heads;
@@ -290,6 +327,7 @@ __global__ __launch_bounds__(kJumpThreads) void plan_mark_kernel(
     const int32_t count = min(kJumpTile, n_seq - lo);
     const int32_t entry = tile_entry ? tile_entry[blockIdx.x] : 0;
     copy_tile<kJumpThreads>(next + lo, s_jump[0], count);
+    pad_tile(s_jump[0], lo, count);
     for (int32_t k = (int32_t)threadIdx.x; k < count; k += kJumpThreads) s_mark[k] = (uint8_t)(lo + k == entry);
     if (threadIdx.x == 0) {
         s_heads[0] = (uint16_t)max(entry - lo, 0);
@@ -314,7 +352,7 @@ __global__ __launch_bounds__(kJumpThreads) void plan_mark_kernel(
                 const unsigned long long found = __ballot(inside);
                 if (found != 0ull && lane_id() == 63 - __builtin_clzll(found)) atomicMax(&s_n_heads, n_heads + i + 1);
             }
-            const bool more = jump_round<false, kJumpThreads>(s_jump[cur], s_jump[cur ^ 1], nullptr, lo, count);
+            const bool more = jump_round_tile(s_jump[cur], s_jump[cur ^ 1], lo, count);
             cur ^= 1;
             const bool any_inside = __syncthreads_or(more ? 1 : 0) != 0;
             const int32_t now = s_n_heads;
