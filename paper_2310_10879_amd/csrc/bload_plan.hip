@@ -19,7 +19,8 @@
 // notes where the orbit enters each tile (one hop per tile); every tile then
 // marks its heads from its entry by jumping in LDS again.  Seven launches at any size; five
 // up to 8192 sequences, where the one tile is entered at position 0 and the first two of the
-// three steps fall away.
+// three steps fall away; six up to 256 tiles of 8192, where every tile follows exit[] to its own
+// entry.
 #include "bload_common.hpp"
 #include "bload_order.hpp"
 
@@ -31,6 +32,7 @@ constexpr int kJumpThreads = 512;                 // workgroup size where a work
                                                   // LDS look-ups of one wave hide behind the others')
 constexpr int kJumpItems = 16;                    // positions per thread there
 constexpr int kJumpTile = kJumpThreads * kJumpItems;   // 8192
+constexpr int kWalkTiles = 256;                   // up to this many jump tiles, each finds its own entry (see plan_mark_kernel)
 constexpr int kJumpRounds = 13;                   // 2^13 = kJumpTile: rounds that cross a whole tile
 constexpr int kScanPerJump = kJumpTile / kTile;   // scan tiles in a jump tile
 constexpr int kWavesPerScanTile = kTile / (kWave * kJumpItems);     // waves of the marking kernel per scan tile
@@ -305,8 +307,10 @@ __global__ __launch_bounds__(kThreads) void plan_chain_kernel(const int32_t* __r
     }
 }
 
-// The heads inside a jump tile, from the position where the orbit enters it (`tile_entry` null:
-// there is one tile only, entered at position 0).  The heads found so far are kept as a list in
+// The heads inside a jump tile, from the position where the orbit enters it: tile_entry[tile],
+// or, with `tile_entry` null, found here by following exit[] from position 0 (at most one hop per
+// tile in front of this one: for few tiles that is quicker than a launch that does it for all;
+// `exit_of` null as well: there is one tile only, entered at position 0).  The heads found so far are kept as a list in
 // orbit order, h_0 = the entry: round r jumps every position of the tile from next^(2^r) to
 // next^(2^(r+1)) as the exit kernel does, and before that the first 2^r heads look up theirs,
 // which are h_(2^r) .. h_(2^(r+1) - 1) where those still lie inside the tile (an orbit only
@@ -314,7 +318,8 @@ __global__ __launch_bounds__(kThreads) void plan_chain_kernel(const int32_t* __r
 // adds no head ends the search.  Also, for each of its scan tiles (one per wave), the number of heads
 // and the last head.
 __global__ __launch_bounds__(kJumpThreads) void plan_mark_kernel(
-    const int32_t* __restrict__ next, const int32_t* __restrict__ tile_entry, int32_t n_seq,
+    const int32_t* __restrict__ next, const int32_t* __restrict__ tile_entry,
+    const int32_t* __restrict__ exit_of, int32_t n_seq,
     uint8_t* __restrict__ mark, int32_t* __restrict__ tile_cnt, int32_t* __restrict__ tile_head)
 {
     __shared__ __attribute__((aligned(16))) int32_t s_jump[2][kJumpTile];
@@ -325,9 +330,21 @@ __global__ __launch_bounds__(kJumpThreads) void plan_mark_kernel(
     static_assert(kJumpTile <= 65536, "a head's place inside the tile is kept in 16 bits");
     const int32_t lo = (int32_t)blockIdx.x * kJumpTile;
     const int32_t count = min(kJumpTile, n_seq - lo);
-    const int32_t entry = tile_entry ? tile_entry[blockIdx.x] : 0;
+    __shared__ int32_t s_entry;
     copy_tile<kJumpThreads>(next + lo, s_jump[0], count);
     pad_tile(s_jump[0], lo, count);
+    if (threadIdx.x == 0) {
+        int32_t e = 0;
+        if (tile_entry) {
+            e = tile_entry[blockIdx.x];
+        } else if (exit_of) {
+            while (e < lo) e = exit_of[e];            // exit[e] lies in a later tile than e: the walk ends
+            if (e >= lo + count) e = -1;              // the orbit passes over this tile
+        }
+        s_entry = e;
+    }
+    __syncthreads();
+    const int32_t entry = s_entry;
     for (int32_t k = (int32_t)threadIdx.x; k < count; k += kJumpThreads) s_mark[k] = (uint8_t)(lo + k == entry);
     if (threadIdx.x == 0) {
         s_heads[0] = (uint16_t)max(entry - lo, 0);
@@ -629,15 +646,17 @@ extern "C" bload_status bload_plan(const int32_t* d_lengths, int64_t n_seq, int3
                            prefix);
         hipLaunchKernelGGL(plan_next_kernel, dim3((uint32_t)ceil_div(n_seq, kThreads)), block, 0, stream,
                            prefix, n, t_blk, next);
-        // where the orbit of position 0 enters each jump tile; a single tile it enters at 0
-        const bool one_jump_tile = l.n_jump_tiles == 1;
-        if (!one_jump_tile) {
+        // where the orbit of position 0 enters each jump tile: a single tile it enters at 0; up to
+        // kWalkTiles tiles every tile finds its own entry; beyond, one thread finds them all
+        const bool one_jump_tile = l.n_jump_tiles == 1, tiles_walk = l.n_jump_tiles <= kWalkTiles;
+        if (!one_jump_tile)
             hipLaunchKernelGGL(plan_exit_kernel, jump_tiles, dim3(kJumpThreads), 0, stream, next, n, exit_of);
+        if (!tiles_walk)
             hipLaunchKernelGGL(plan_chain_kernel, dim3(1), block, 0, stream, exit_of, n, l.n_jump_tiles,
                                tile_entry);
-        }
         hipLaunchKernelGGL(plan_mark_kernel, jump_tiles, dim3(kJumpThreads), 0, stream, next,
-                           one_jump_tile ? nullptr : tile_entry, n, mark, tile_cnt, tile_head);
+                           tiles_walk ? nullptr : tile_entry, one_jump_tile ? nullptr : exit_of, n, mark,
+                           tile_cnt, tile_head);
         hipLaunchKernelGGL(plan_assign_kernel, tiles, block, 0, stream, mark, d_order, prefix, n,
                            tile_cnt, tile_head, tile_bad, d_block_of_seq, d_offset_of_seq,
                            d_block_first, result);
