@@ -26,6 +26,19 @@ def test_plan_matches_oracle(kind, n, T):
         assert_plan_equal(gpu_plan(L, T, seed), ref, n)
 
 
+@pytest.mark.parametrize("case", range(16))
+def test_plan_random_sizes_of_several_jump_tiles(case):
+    # 2 .. 37 tiles of 8192 positions: every tile finds where the orbit of position 0 enters it
+    rng = np.random.default_rng(9000 + case)
+    n = int(rng.integers(8193, 300000))
+    T = int(rng.choice([1, 3, 64, 600, 4096, 100000]))
+    kind = str(rng.choice(["uniform", "short", "long", "mixed"]))
+    L = workloads.random_lengths(rng, n, T, kind)
+    seed = int(rng.integers(0, 2 ** 63))
+    print(f"plan n={n} T={T} kind={kind} seed={seed}", flush=True)
+    assert_plan_equal(gpu_plan(L, T, seed), oracle.plan(L, T, oracle.order(n, seed)), n)
+
+
 @pytest.mark.parametrize("wid", [1, 2, 3, 4, 5])
 def test_plan_workloads_full_size(wid):
     w = workloads.WORKLOADS[wid]
