@@ -27,6 +27,25 @@ inline bload_status launch_status()
     return hip_ok(hipGetLastError()) ? BLOAD_OK : BLOAD_EHIP;
 }
 
+// 64 bytes of pinned host memory per calling thread, made at the thread's first call and kept
+// until the process ends; null if it cannot be had.  An entry point whose caller waits for a few
+// numbers lets its last kernel write them there, so that only the wait for the stream follows
+// the launches (a copy back from device memory costs about 9 us more per call).  Only for plain
+// stores by one kernel: nothing that kernels read back or update atomically.
+inline void* host_result_buffer()
+{
+    static thread_local void* mem = nullptr;
+    static thread_local bool tried = false;
+    if (!tried) {
+        tried = true;
+        if (hipHostMalloc(&mem, 64, hipHostMallocPortable) != hipSuccess) {
+            mem = nullptr;
+            (void)hipGetLastError();
+        }
+    }
+    return mem;
+}
+
 inline bool aligned_to(const void* p, size_t a)
 {
     return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0;

@@ -616,7 +616,11 @@ extern "C" bload_status bload_plan(const int32_t* d_lengths, int64_t n_seq, int3
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     uint8_t* ws = static_cast<uint8_t*>(d_workspace);
-    PlanResult* result = reinterpret_cast<PlanResult*>(ws + l.result);
+    // the numbers the host waits for go straight into pinned host memory where there is some,
+    // else into the workspace, from where they are copied back
+    static_assert(sizeof(PlanResult) <= 64, "the pinned buffer holds 64 bytes");
+    PlanResult* pinned = static_cast<PlanResult*>(host_result_buffer());
+    PlanResult* result = pinned ? pinned : reinterpret_cast<PlanResult*>(ws + l.result);
     int32_t* shuffled_len = reinterpret_cast<int32_t*>(ws + l.shuffled_len);
     int64_t* prefix = reinterpret_cast<int64_t*>(ws + l.prefix);
     int32_t* next = reinterpret_cast<int32_t*>(ws + l.next);
@@ -664,9 +668,10 @@ extern "C" bload_status bload_plan(const int32_t* d_lengths, int64_t n_seq, int3
     if (launch_status() != BLOAD_OK) return BLOAD_EHIP;
 
     PlanResult host{};
-    if (!hip_ok(hipMemcpyAsync(&host, result, sizeof(host), hipMemcpyDeviceToHost, stream)))
+    if (!pinned && !hip_ok(hipMemcpyAsync(&host, result, sizeof(host), hipMemcpyDeviceToHost, stream)))
         return BLOAD_EHIP;
     if (!hip_ok(hipStreamSynchronize(stream))) return BLOAD_EHIP;
+    if (pinned) host = *pinned;
     if (host.bad_length) return BLOAD_ELENGTH;
     *h_num_blocks = host.num_blocks;
     *h_total_frames = host.total_frames;

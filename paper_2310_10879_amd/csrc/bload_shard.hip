@@ -99,7 +99,8 @@ extern "C" bload_status bload_plan_shard(const int32_t* d_order, const int32_t* 
     if (workspace_bytes < 16) return BLOAD_EWORKSPACE;
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    int64_t* n_local = static_cast<int64_t*>(d_workspace);
+    int64_t* pinned = static_cast<int64_t*>(host_result_buffer());
+    int64_t* n_local = pinned ? pinned : static_cast<int64_t*>(d_workspace);
     hipLaunchKernelGGL(shard_block_first_kernel, dim3(1), dim3(kThreads), 0, stream, d_block_first,
                        num_blocks, rank, world, blocks_local, d_block_first_local, n_local);
     hipLaunchKernelGGL(shard_fill_kernel, dim3((uint32_t)ceil_div(n_seq, kThreads)), dim3(kThreads), 0,
@@ -107,9 +108,9 @@ extern "C" bload_status bload_plan_shard(const int32_t* d_order, const int32_t* 
                        (int32_t)n_seq, blocks_local, rank, world, d_order_local, d_block_of_seq_local);
     if (launch_status() != BLOAD_OK) return BLOAD_EHIP;
     int64_t host = 0;
-    if (!hip_ok(hipMemcpyAsync(&host, n_local, sizeof(host), hipMemcpyDeviceToHost, stream)))
+    if (!pinned && !hip_ok(hipMemcpyAsync(&host, n_local, sizeof(host), hipMemcpyDeviceToHost, stream)))
         return BLOAD_EHIP;
     if (!hip_ok(hipStreamSynchronize(stream))) return BLOAD_EHIP;
-    *h_n_seq_local = host;
+    *h_n_seq_local = pinned ? *pinned : host;
     return BLOAD_OK;
 }
