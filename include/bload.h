@@ -105,7 +105,9 @@ int bload_last_hip_error(void);
  *
  * Lengths are checked on the device; a bad one gives BLOAD_ELENGTH.  n_seq = 0
  * gives B = 0, BLOAD_OK, and writes nothing to the device.  Synchronises the
- * stream before returning.
+ * stream before returning.  The library keeps 64 bytes of pinned host memory per
+ * calling thread (taken at that thread's first call, never freed) into which the
+ * device writes B and the frame total; bload_plan_shard uses the same bytes.
  */
 size_t bload_plan_workspace_bytes(int64_t n_seq);
 
